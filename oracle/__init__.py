@@ -1,0 +1,208 @@
+"""CPU oracle of the MoE layer and of the chunked / layered schedules -- TEST INFRASTRUCTURE.
+
+Only tests, the smoke check and the benchmark's cpu_baseline leg may import this
+package.  It wraps `moe_oracle.c` (plain fp64 C, built by `oracle/build.py`)
+with numpy marshalling; it shares nothing with the GPU library and never
+imports it.
+
+Arrays are numpy: float64, float32, or uint16 holding bfloat16 bit patterns
+(widened exactly to fp64 inside the C code).
+"""
+import ctypes
+import os
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "liboracle.so")
+_lib = None
+
+F64, F32, BF16 = 0, 1, 2
+SCHED_CHUNKED, SCHED_LAYERED = 0, 1
+
+
+class OracleError(RuntimeError):
+    pass
+
+
+class _Counters(ctypes.Structure):
+    _fields_ = [("expert_bytes", ctypes.c_uint64), ("router_bytes", ctypes.c_uint64),
+                ("active_experts_total", ctypes.c_uint64), ("tokens_processed", ctypes.c_uint64),
+                ("iterations", ctypes.c_uint32), ("layer_passes", ctypes.c_uint32)]
+
+
+@dataclass
+class Counters:
+    expert_bytes: int
+    router_bytes: int
+    active_experts_total: int
+    tokens_processed: int
+    iterations: int
+    layer_passes: int
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            from . import build as _b
+            _b.build()
+        L = ctypes.CDLL(_LIB_PATH)
+        L.orc_round_bf16.restype = ctypes.c_double
+        L.orc_round_bf16.argtypes = [ctypes.c_double]
+        L.orc_round_f32.restype = ctypes.c_double
+        L.orc_round_f32.argtypes = [ctypes.c_double]
+        L.orc_num_threads.restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def num_threads() -> int:
+    return int(lib().orc_num_threads())
+
+
+def _dt(a: np.ndarray) -> int:
+    if a.dtype == np.float64:
+        return F64
+    if a.dtype == np.float32:
+        return F32
+    if a.dtype == np.uint16:
+        return BF16
+    raise TypeError(f"oracle takes float64, float32 or uint16 (bf16 bits), not {a.dtype}")
+
+
+def _c(a, dtype=None):
+    a = np.ascontiguousarray(a) if dtype is None else np.ascontiguousarray(a, dtype=dtype)
+    return a
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise OracleError(f"{what}: oracle error {rc} "
+                          f"({ {1: 'bad argument', 2: 'non-finite logit', 3: 'allocation'}.get(rc, '?')})")
+
+
+def round_bf16(a):
+    """Round float64 values to the nearest bfloat16 (ties to even); returns float64."""
+    f = np.vectorize(lib().orc_round_bf16, otypes=[np.float64])
+    return f(np.asarray(a, dtype=np.float64))
+
+
+def router_topk(x, w_router, bias, k, renormalize=True, want_logits=False, want_gap=False):
+    """x [T,H], w_router [E,H], bias [E] float32 or None -> idx [T,k] int32, w [T,k] f64 (+ logits, gap)."""
+    x, w_router = _c(x), _c(w_router)
+    T, H = x.shape
+    E = w_router.shape[0]
+    assert w_router.shape == (E, H)
+    b = None if bias is None else _c(bias, np.float32)
+    idx = np.zeros((T, k), dtype=np.int32)
+    w = np.zeros((T, k), dtype=np.float64)
+    logits = np.zeros((T, E), dtype=np.float64) if want_logits else None
+    gap = np.zeros((T,), dtype=np.float64) if want_gap else None
+    rc = lib().orc_router_topk(_p(x), _dt(x), ctypes.c_int64(T), ctypes.c_int64(H), _p(w_router),
+                               _dt(w_router), _p(b), E, k, int(bool(renormalize)),
+                               _p(idx), _p(w), _p(logits), _p(gap))
+    _check(rc, "router_topk")
+    out = [idx, w]
+    if want_logits:
+        out.append(logits)
+    if want_gap:
+        out.append(gap)
+    return tuple(out)
+
+
+def permute(idx, E):
+    """idx [T,k] int32 -> counts [E], offsets [E+1], perm [T*k], inv [T*k] (all int32)."""
+    idx = _c(idx, np.int32)
+    T, k = idx.shape
+    counts = np.zeros(E, dtype=np.int32)
+    offsets = np.zeros(E + 1, dtype=np.int32)
+    perm = np.zeros(T * k, dtype=np.int32)
+    inv = np.zeros(T * k, dtype=np.int32)
+    rc = lib().orc_permute(_p(idx), ctypes.c_int64(T), k, E, _p(counts), _p(offsets), _p(perm), _p(inv))
+    _check(rc, "permute")
+    return counts, offsets, perm, inv
+
+
+def moe_layer(x, w_router, bias, w_gate_up, w_down, k, renormalize=True, residual=False):
+    """One MoE layer.  x [T,H]; w_router [E,H]; w_gate_up [E,2I,H]; w_down [E,H,I].
+
+    Returns y [T,H] f64 (unrounded), idx [T,k] int32, w [T,k] f64.
+    """
+    x, w_router, w_gate_up, w_down = _c(x), _c(w_router), _c(w_gate_up), _c(w_down)
+    T, H = x.shape
+    E = w_router.shape[0]
+    I = w_down.shape[2]
+    assert w_router.shape == (E, H) and w_gate_up.shape == (E, 2 * I, H) and w_down.shape == (E, H, I)
+    wdt = _dt(w_router)
+    assert _dt(w_gate_up) == wdt and _dt(w_down) == wdt
+    b = None if bias is None else _c(bias, np.float32)
+    y = np.zeros((T, H), dtype=np.float64)
+    idx = np.zeros((T, k), dtype=np.int32)
+    w = np.zeros((T, k), dtype=np.float64)
+    rc = lib().orc_moe_layer(_p(x), _dt(x), ctypes.c_int64(T), ctypes.c_int64(H), _p(w_router), _p(b),
+                             _p(w_gate_up), _p(w_down), wdt, E, k, ctypes.c_int64(I),
+                             int(bool(renormalize)), int(bool(residual)), _p(y), _p(idx), _p(w))
+    _check(rc, "moe_layer")
+    return y, idx, w
+
+
+def group_forward(layers, x_decode, x_prefill, k, schedule, chunk=0, renormalize=True, residual=True,
+                  act_dtype=None, want_trace=False):
+    """A contiguous layer group under `schedule` ("chunked" with `chunk`, or "layered").
+
+    layers: list of dicts with w_router [E,H], router_bias ([E] float32 or None),
+    w_gate_up [E,2I,H], w_down [E,H,I].  x_decode [D,H], x_prefill [P,H].
+    act_dtype: format activations are rounded to between layers (default: that of x).
+    Returns y_decode [D,H] f64, y_prefill [P,H] f64, Counters (and the routing trace).
+    """
+    n = len(layers)
+    Wr = [_c(l["w_router"]) for l in layers]
+    Wgu = [_c(l["w_gate_up"]) for l in layers]
+    Wd = [_c(l["w_down"]) for l in layers]
+    Bs = [None if l.get("router_bias") is None else _c(l["router_bias"], np.float32) for l in layers]
+    E, H = Wr[0].shape
+    I = Wd[0].shape[2]
+    wdt = _dt(Wr[0])
+    for a, b_, c_ in zip(Wr, Wgu, Wd):
+        assert a.shape == (E, H) and b_.shape == (E, 2 * I, H) and c_.shape == (E, H, I)
+        assert _dt(a) == wdt and _dt(b_) == wdt and _dt(c_) == wdt
+    x_decode, x_prefill = _c(x_decode), _c(x_prefill)
+    D, P = x_decode.shape[0], x_prefill.shape[0]
+    if D and P:
+        assert x_decode.dtype == x_prefill.dtype
+    xsrc = x_decode if D else x_prefill
+    xdt = _dt(xsrc)
+    if act_dtype is None:
+        act_dtype = xdt
+    sched = {"chunked": SCHED_CHUNKED, "layered": SCHED_LAYERED}[schedule]
+    VP = ctypes.c_void_p * n
+    FP = ctypes.c_void_p * n
+    wr_arr = VP(*[a.ctypes.data for a in Wr])
+    gu_arr = VP(*[a.ctypes.data for a in Wgu])
+    d_arr = VP(*[a.ctypes.data for a in Wd])
+    b_arr = FP(*[None if b_ is None else b_.ctypes.data for b_ in Bs])
+    y_decode = np.zeros((D, H), dtype=np.float64)
+    y_prefill = np.zeros((P, H), dtype=np.float64)
+    ctr = _Counters()
+    trace = None
+    if want_trace:
+        step = P if (schedule == "layered" or P == 0) else chunk
+        n_iter = 1 if P == 0 else -(-P // max(step, 1))
+        trace = np.zeros(((n_iter * D + P) * n * k,), dtype=np.int32)
+    rc = lib().orc_group_forward(wr_arr, b_arr, gu_arr, d_arr, wdt, n, ctypes.c_int64(H), E, k,
+                                 ctypes.c_int64(I), int(bool(renormalize)), int(bool(residual)),
+                                 int(act_dtype), _p(x_decode), ctypes.c_int64(D), _p(x_prefill),
+                                 ctypes.c_int64(P), xdt, sched, ctypes.c_int64(chunk),
+                                 _p(y_decode), _p(y_prefill), ctypes.byref(ctr), _p(trace))
+    _check(rc, "group_forward")
+    c = Counters(ctr.expert_bytes, ctr.router_bytes, ctr.active_experts_total, ctr.tokens_processed,
+                 ctr.iterations, ctr.layer_passes)
+    if want_trace:
+        return y_decode, y_prefill, c, trace
+    return y_decode, y_prefill, c

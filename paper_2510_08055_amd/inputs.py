@@ -1,0 +1,119 @@
+"""Seeded synthetic inputs shaped like the layered-prefill paper's workloads.
+
+This module only draws random tensors and names workload shapes.  It holds none
+of the MoE layer's arithmetic, so both the CPU oracle's tests and the GPU
+library's tests can take their inputs from it without sharing method code.
+
+Recipe (the paper's traces and trained weights are not available; Table 3 gives
+the shapes E / top-k / hidden size, Sec. 3.2 the 8192-token prompt, Sec. 4.4 the
+512-token chunk, Sec. 3.1 the decode batch sizes):
+  hidden states  ~ N(0, 1)
+  router, gate_up and down weights ~ N(0, 0.02)
+each drawn in fp32 from a generator seeded by (seed, tensor name, layer) and
+then rounded ONCE to the workload dtype; every consumer sees those exact bits.
+Tensors can be drawn on the CPU or directly on the GPU (large weights); the two
+devices give different, individually reproducible, streams.
+"""
+import zlib
+from dataclasses import dataclass, replace
+from typing import Optional
+
+import numpy as np
+import torch
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    H: int            # hidden size
+    E: int            # experts
+    K: int            # experts per token (top-k)
+    I: int            # expert intermediate size
+    n_layers: int
+    D: int            # decode tokens
+    P: int            # prefill tokens
+    dtype: str        # "bf16" | "f32"
+    chunk: int = 0    # chunk size used when the chunked schedule is run
+    seed: int = 0
+    zipf_s: float = 0.0   # > 0: router bias shaped so expert shares follow Zipf(s)
+    residual: bool = True
+
+
+# The five benchmark workloads, in the order of the baseline description.
+WORKLOADS = {
+    "tiny_f32": Workload("tiny_f32", H=256, E=8, K=2, I=512, n_layers=1, D=0, P=64, dtype="f32",
+                         chunk=16, seed=0, residual=False),
+    "qwen3_layer": Workload("qwen3_layer", H=2048, E=128, K=8, I=768, n_layers=1, D=64, P=2048,
+                            dtype="bf16", chunk=512, seed=1, residual=False),
+    "qwen3_group8": Workload("qwen3_group8", H=2048, E=128, K=8, I=768, n_layers=8, D=128, P=8192,
+                             dtype="bf16", chunk=512, seed=2),
+    "mixtral_zipf": Workload("mixtral_zipf", H=4096, E=8, K=2, I=14336, n_layers=1, D=32, P=4096,
+                             dtype="bf16", chunk=512, seed=3, zipf_s=1.2, residual=False),
+    "decode_large": Workload("decode_large", H=2880, E=128, K=4, I=2880, n_layers=4, D=256, P=0,
+                             dtype="bf16", chunk=512, seed=4),
+}
+
+
+def scaled(w: Workload, **kw) -> Workload:
+    """A copy of a workload with some fields replaced (smaller test versions)."""
+    return replace(w, **kw)
+
+
+def torch_dtype(name: str) -> torch.dtype:
+    return {"bf16": torch.bfloat16, "f32": torch.float32}[name]
+
+
+def _stream_seed(seed: int, name: str, layer: int) -> int:
+    return (zlib.crc32(f"{name}/{layer}".encode()) ^ (seed * 0x9E3779B1)) & 0x7FFFFFFF
+
+
+def randn(shape, std: float, seed: int, name: str, layer: int = 0, dtype: str = "bf16",
+          device: str = "cpu") -> torch.Tensor:
+    """N(0, std) drawn in fp32 on `device`, rounded once to `dtype`."""
+    g = torch.Generator(device=device)
+    g.manual_seed(_stream_seed(seed, name, layer))
+    numel = int(np.prod(shape)) if len(shape) else 1
+    out = torch.empty(shape, dtype=torch_dtype(dtype), device=device)
+    flat = out.view(-1)
+    step = 1 << 27      # draw in slices so the fp32 temporary stays small
+    for s in range(0, numel, step):
+        n = min(step, numel - s)
+        flat[s:s + n] = (torch.randn(n, generator=g, device=device, dtype=torch.float32) * std).to(out.dtype)
+    return out
+
+
+def zipf_shares(E: int, s: float) -> np.ndarray:
+    """Target per-expert assignment shares p_e proportional to rank^-s, rank = e+1."""
+    p = np.arange(1, E + 1, dtype=np.float64) ** (-s)
+    return p / p.sum()
+
+
+def make_layer(w: Workload, layer: int, device: str = "cpu", router_bias: Optional[torch.Tensor] = None):
+    """Random weights of one MoE layer: dict of w_router [E,H], router_bias, w_gate_up [E,2I,H], w_down [E,H,I]."""
+    return {
+        "w_router": randn((w.E, w.H), 0.02, w.seed, "w_router", layer, w.dtype, device),
+        "router_bias": router_bias,
+        "w_gate_up": randn((w.E, 2 * w.I, w.H), 0.02, w.seed, "w_gate_up", layer, w.dtype, device),
+        "w_down": randn((w.E, w.H, w.I), 0.02, w.seed, "w_down", layer, w.dtype, device),
+    }
+
+
+def make_hidden(w: Workload, device: str = "cpu"):
+    """(x_decode [D,H], x_prefill [P,H]) ~ N(0,1)."""
+    xd = randn((w.D, w.H), 1.0, w.seed, "x_decode", 0, w.dtype, device)
+    xp = randn((w.P, w.H), 1.0, w.seed, "x_prefill", 0, w.dtype, device)
+    return xd, xp
+
+
+def to_numpy(t: Optional[torch.Tensor]) -> Optional[np.ndarray]:
+    """Host copy for the oracle: float32/float64 as they are, bfloat16 as uint16 bit patterns."""
+    if t is None:
+        return None
+    t = t.detach().cpu().contiguous()
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).numpy().view(np.uint16)
+    return t.numpy()
+
+
+def layer_to_numpy(layer: dict) -> dict:
+    return {k: to_numpy(v) for k, v in layer.items()}
