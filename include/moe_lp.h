@@ -1,0 +1,166 @@
+/*
+ * moe_lp.h -- C ABI of the MI355X (gfx950) MoE expert-FFN hot path that layered
+ * prefill speeds up: router + top-k, token permutation, grouped SwiGLU FFN,
+ * weighted combine, and a layer-group driver for the chunked and the layered
+ * prefill schedules.
+ *
+ * General conventions
+ *   - Every data pointer is a DEVICE pointer owned by the caller unless a
+ *     parameter says "host".  Base pointers must be 16-byte aligned.
+ *   - Tensors are dense row-major.  "dtype" elements are bfloat16 (2 bytes) or
+ *     float (4 bytes) as chosen in moe_config.dtype.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls enqueue work on it and return; nothing synchronises with the host
+ *     except moe_read_counters.
+ *   - The library allocates no device memory: all scratch lives in the
+ *     workspace handed to moe_create.  Calls on one moe_ctx must not overlap
+ *     in time (they share that workspace); use one ctx per concurrent stream.
+ *   - Every failure is a return code; argument errors are detected on the host
+ *     before anything is launched.  Outputs are fully overwritten on success.
+ *   - A zero token count is a legal no-op.
+ */
+#ifndef MOE_LP_H
+#define MOE_LP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct moe_ctx moe_ctx; /* opaque, host memory, owned by the library */
+
+typedef enum {
+    MOE_OK = 0,
+    MOE_ERR_NULL = 1,      /* a required pointer is NULL */
+    MOE_ERR_SHAPE = 2,     /* a size is negative / zero / inconsistent (k > E, T > max_tokens ...) */
+    MOE_ERR_DTYPE = 3,     /* unknown moe_dtype */
+    MOE_ERR_ALIGN = 4,     /* H or I not a multiple of 8, or a pointer not 16-byte aligned */
+    MOE_ERR_WORKSPACE = 5, /* workspace smaller than moe_workspace_bytes says */
+    MOE_ERR_SCHEDULE = 6,  /* unknown schedule kind, or chunk <= 0 for a chunked schedule */
+    MOE_ERR_DEVICE = 7     /* a HIP runtime call failed (launch error, wrong device ...) */
+} moe_status;
+
+typedef enum { MOE_F32 = 0, MOE_BF16 = 1 } moe_dtype;
+
+/* Shape of one MoE layer (Table 3 gives E, K and H of the evaluated models). */
+typedef struct {
+    int32_t H;           /* hidden size, multiple of 8 */
+    int32_t E;           /* number of experts, 1..1024 */
+    int32_t K;           /* experts per token (top-k), 1..min(E,64) */
+    int32_t I;           /* expert intermediate size, multiple of 8 */
+    int32_t dtype;       /* moe_dtype of activations and weights */
+    int32_t renormalize; /* 1: mixing weights of the K selected experts are divided by their sum */
+    int32_t residual;    /* 1: moe_group_forward links layers by x <- x + MoE(x); 0: x <- MoE(x) */
+} moe_config;
+
+/* Weights of one layer (device pointers). */
+typedef struct {
+    const void *w_router;     /* [E, H]     dtype */
+    const float *router_bias; /* [E] fp32 added to the logits, or NULL */
+    const void *w_gate_up;    /* [E, 2I, H] dtype; rows [0,I) gate projection, rows [I,2I) up projection */
+    const void *w_down;       /* [E, H, I]  dtype */
+} moe_layer;
+
+typedef enum { MOE_SCHED_CHUNKED = 0, MOE_SCHED_LAYERED = 1 } moe_sched_kind;
+typedef struct {
+    int32_t kind;  /* moe_sched_kind */
+    int32_t chunk; /* prefill tokens per iteration; > 0 when kind == MOE_SCHED_CHUNKED, ignored otherwise */
+} moe_schedule;
+
+/* Expert-weight traffic model, accumulated by moe_group_forward (Sec. 5.4: a load
+ * byte is counted whenever an expert's parameters are brought in for execution). */
+typedef struct {
+    uint64_t expert_bytes;         /* sum over (iteration, layer) of active experts * 3*H*I*sizeof(dtype) */
+    uint64_t router_bytes;         /* sum over (iteration, layer) of E*H*sizeof(dtype) */
+    uint64_t active_experts_total; /* sum over (iteration, layer) of experts with >= 1 token */
+    uint64_t tokens_processed;     /* sum over iterations of the batch rows of that iteration */
+    uint32_t iterations;
+    uint32_t layer_passes;         /* iterations * n_layers */
+} moe_counters;
+
+/* Bytes of device workspace a context for batches of up to max_tokens rows needs. Host-only. */
+moe_status moe_workspace_bytes(const moe_config *cfg, int64_t max_tokens, size_t *out_bytes);
+
+/* Create a context over a caller-owned device workspace (256-byte aligned, at least
+ * moe_workspace_bytes; it must stay alive and untouched until moe_destroy).  The
+ * workspace's counter block is cleared on `stream`. */
+moe_status moe_create(const moe_config *cfg, int64_t max_tokens, void *workspace, size_t workspace_bytes,
+                      void *stream, moe_ctx **out_ctx);
+moe_status moe_destroy(moe_ctx *ctx);
+
+/*
+ * Router (Sec. 2.4: "routes tokens to a small subset of ... experts, via routers").
+ *   logits z[t,e] = sum_h x[t,h]*w_router[e,h] (+ bias[e]), accumulated in fp64;
+ *   topk_idx[t,:] = the K experts with the largest logits, ordered by logit descending,
+ *                   equal logits by ascending expert index;
+ *   topk_w[t,j]   = softmax over all E logits evaluated at the selected experts, divided by
+ *                   the sum over the K selected ones when cfg.renormalize.
+ * x [T,H] dtype, w_router [E,H] dtype, bias [E] fp32 or NULL -> topk_idx [T,K] int32, topk_w [T,K] fp32.
+ * Routing of a token does not depend on which other tokens are in the batch.
+ */
+moe_status moe_router_topk(moe_ctx *ctx, const void *x, int64_t T, const void *w_router, const float *bias,
+                           int32_t *topk_idx, float *topk_w, void *stream);
+
+/*
+ * Token permutation (Sec. 3.1: the tokens routed to each expert form that expert's batch).
+ * The T*K assignments (t, j) are listed by expert, then token, then slot:
+ *   counts [E], offsets [E+1] (exclusive running sum, offsets[E] = T*K),
+ *   perm [T*K]: perm[r] = t*K + j is the assignment held by permuted row r,
+ *   inv_perm [T*K]: inv_perm[perm[r]] = r,
+ *   x_perm [T*K, H] dtype (optional, may be NULL): x_perm[r,:] = x[perm[r] / K, :].
+ * topk_idx entries must lie in [0, E).  The order is deterministic (a stable sort).
+ */
+moe_status moe_permute(moe_ctx *ctx, const void *x, const int32_t *topk_idx, int64_t T,
+                       int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv_perm,
+                       void *x_perm, void *stream);
+
+/*
+ * Grouped expert FFN (Sec. 2.1: FC layers with a SwiGLU non-linearity; Sec. 2.5: each expert's
+ * FC runs over the tokens routed to it).  For expert e and rows r in [offsets[e], offsets[e+1]):
+ *   g = x_perm[r,:] . w_gate_up[e, 0:I, :]^T,  u = x_perm[r,:] . w_gate_up[e, I:2I, :]^T,
+ *   a = g / (1 + exp(-g)) * u   (rounded once to dtype),  y_perm[r,:] = a . w_down[e]^T.
+ * x_perm [A,H] dtype, offsets [E+1] int32 (device), A = offsets[E] rows -> y_perm [A,H] dtype.
+ * Experts with no rows cause no weight reads.  bf16 inputs accumulate in fp32 on the matrix cores.
+ */
+moe_status moe_grouped_ffn(moe_ctx *ctx, const void *x_perm, const int32_t *offsets, int64_t A,
+                           const void *w_gate_up, const void *w_down, void *y_perm, void *stream);
+
+/*
+ * Weighted un-permute and combine (Sec. 2.4: a token's output mixes its selected experts):
+ *   y[t,:] = sum_{j<K} topk_w[t,j] * y_perm[inv_perm[t*K+j], :]  (+ residual[t,:]),
+ * summed in fp32 in slot order and rounded once.  residual [T,H] dtype or NULL; y may alias residual.
+ */
+moe_status moe_combine(moe_ctx *ctx, const void *y_perm, const int32_t *inv_perm, const float *topk_w,
+                       const void *residual, int64_t T, void *y, void *stream);
+
+/*
+ * A contiguous layer group over a hybrid batch (Sec. 2.3), under one of the two schedules:
+ *   layered (Sec. 4.1-4.2): ONE iteration; rows [x_decode; x_prefill] cross layers 0..n_layers-1 once.
+ *   chunked(C) (Sec. 2.3):  ceil(P/C) iterations; iteration c sends [x_decode; x_prefill[cC : min((c+1)C,P)]]
+ *                           through all layers, so every chunk re-streams the experts it activates.
+ * P = 0 gives exactly one decode-only iteration under either schedule.  Per layer the four steps above
+ * run in order, x <- (x +) MoE_l(x), activations held in dtype between layers.  y_decode [D,H] holds the
+ * decode rows' result (identical in every iteration), y_prefill [P,H] the prompt rows'.  Inputs are not
+ * modified.  layers is a HOST array of n_layers structs of device pointers.  D + P per iteration must
+ * not exceed the context's max_tokens.  Counters accumulate until moe_reset_counters.
+ */
+moe_status moe_group_forward(moe_ctx *ctx, const moe_layer *layers, int32_t n_layers,
+                             const void *x_decode, int64_t D, const void *x_prefill, int64_t P,
+                             moe_schedule sched, void *y_decode, void *y_prefill, void *stream);
+
+/* Copy the counters to host memory `out`; synchronises `stream`. */
+moe_status moe_read_counters(moe_ctx *ctx, moe_counters *out, void *stream);
+moe_status moe_reset_counters(moe_ctx *ctx, void *stream);
+
+/* Name of the gate_up GEMM kernel variant the context would use for a batch of T rows (host string,
+ * static storage): lets a benchmark label its roofline line. */
+const char *moe_ffn_variant(const moe_ctx *ctx, int64_t T);
+
+const char *moe_status_string(moe_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_LP_H */

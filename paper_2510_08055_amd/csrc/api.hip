@@ -1,0 +1,318 @@
+// C ABI of the MoE hot path: argument checks, workspace carving and the layer-group driver
+// for the chunked (Sec. 2.3) and layered (Sec. 4.1-4.2) prefill schedules.  All arithmetic
+// happens in the kernels of router.hip / permute.hip / ffn.hip / combine.hip.
+#include <new>
+
+#include "common.h"
+
+using namespace moe;
+
+struct moe_ctx {
+    moe_config cfg;
+    int64_t max_tokens;
+    int esz;  // bytes per element
+    // workspace slices (device)
+    unsigned long long* d_active_total;
+    double* logits;
+    int32_t *idx, *counts, *offsets, *perm, *inv, *tile_hist;
+    float* w;
+    void *xa, *xb, *act, *y_perm;
+    // host-side counters (everything the host already knows)
+    uint64_t router_bytes, tokens_processed;
+    uint32_t iterations, layer_passes;
+};
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t up(size_t n) { return (n + kAlign - 1) / kAlign * kAlign; }
+
+moe_status check_cfg(const moe_config* c)
+{
+    if (!c) return MOE_ERR_NULL;
+    if (c->dtype != MOE_F32 && c->dtype != MOE_BF16) return MOE_ERR_DTYPE;
+    if (c->H <= 0 || c->I <= 0 || c->E <= 0 || c->E > kMaxExperts || c->K <= 0 || c->K > c->E || c->K > kMaxTopK)
+        return MOE_ERR_SHAPE;
+    if (c->H % 8 || c->I % 8) return MOE_ERR_ALIGN;
+    return MOE_OK;
+}
+
+struct Layout {
+    size_t counters, logits, idx, w, counts, offsets, perm, inv, tile_hist, xa, xb, act, y_perm, total;
+};
+
+Layout carve(const moe_config& c, int64_t Tm)
+{
+    const size_t esz = c.dtype == MOE_BF16 ? 2 : 4;
+    const size_t Am = (size_t)Tm * c.K;
+    const size_t n_tiles = (Am + kPermTile - 1) / kPermTile + 1;
+    Layout L;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o += up(bytes); return at; };
+    L.counters = take(256);
+    L.logits = take((size_t)Tm * c.E * sizeof(double));
+    L.idx = take(Am * 4);
+    L.w = take(Am * 4);
+    L.counts = take((size_t)c.E * 4);
+    L.offsets = take((size_t)(c.E + 1) * 4);
+    L.perm = take(Am * 4);
+    L.inv = take(Am * 4);
+    L.tile_hist = take(n_tiles * c.E * 4);
+    L.xa = take((size_t)Tm * c.H * esz);
+    L.xb = take((size_t)Tm * c.H * esz);
+    L.act = take(Am * c.I * esz);
+    L.y_perm = take(Am * c.H * esz);
+    L.total = o;
+    return L;
+}
+
+inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+inline moe_status dev(hipError_t e) { return e == hipSuccess ? MOE_OK : MOE_ERR_DEVICE; }
+
+// One layer on the batch `x` [T,H]; output rows [0,rows0) -> y0, the rest -> y1.
+moe_status run_layer(moe_ctx* c, const moe_layer& L, const void* x, int64_t T, void* y0, int64_t rows0, void* y1,
+                     hipStream_t s)
+{
+    const moe_config& g = c->cfg;
+    const int64_t A = T * g.K;
+    hipError_t e = launch_router_logits(g.dtype, x, T, g.H, L.w_router, L.router_bias, g.E, c->logits, s);
+    if (e != hipSuccess) return MOE_ERR_DEVICE;
+    e = launch_topk(c->logits, T, g.E, g.K, g.renormalize, c->idx, c->w, s);
+    if (e != hipSuccess) return MOE_ERR_DEVICE;
+    e = launch_permute(c->idx, A, g.E, c->counts, c->offsets, c->perm, c->inv, c->tile_hist, c->d_active_total, s);
+    if (e != hipSuccess) return MOE_ERR_DEVICE;
+    // the activation rows are gathered inside the gate_up GEMM's tile loads: no x_perm round trip
+    e = launch_grouped_ffn(g.dtype, x, c->perm, g.K, c->offsets, A, g.E, g.H, g.I, L.w_gate_up, L.w_down, c->act,
+                           c->y_perm, s);
+    if (e != hipSuccess) return MOE_ERR_DEVICE;
+    e = launch_combine(g.dtype, c->y_perm, c->inv, c->w, g.residual ? x : nullptr, T, g.K, g.H, y0, rows0, y1, s);
+    return dev(e);
+}
+
+}  // namespace
+
+extern "C" {
+
+moe_status moe_workspace_bytes(const moe_config* cfg, int64_t max_tokens, size_t* out_bytes)
+{
+    if (!out_bytes) return MOE_ERR_NULL;
+    moe_status st = check_cfg(cfg);
+    if (st != MOE_OK) return st;
+    if (max_tokens <= 0 || max_tokens * (int64_t)cfg->K >= (int64_t)1 << 31) return MOE_ERR_SHAPE;
+    *out_bytes = carve(*cfg, max_tokens).total;
+    return MOE_OK;
+}
+
+moe_status moe_create(const moe_config* cfg, int64_t max_tokens, void* workspace, size_t workspace_bytes,
+                      void* stream, moe_ctx** out_ctx)
+{
+    if (!out_ctx || !workspace) return MOE_ERR_NULL;
+    moe_status st = check_cfg(cfg);
+    if (st != MOE_OK) return st;
+    if (max_tokens <= 0 || max_tokens * (int64_t)cfg->K >= (int64_t)1 << 31) return MOE_ERR_SHAPE;
+    if (reinterpret_cast<uintptr_t>(workspace) % kAlign) return MOE_ERR_ALIGN;
+    const Layout L = carve(*cfg, max_tokens);
+    if (workspace_bytes < L.total) return MOE_ERR_WORKSPACE;
+    moe_ctx* c = new (std::nothrow) moe_ctx();
+    if (!c) return MOE_ERR_DEVICE;
+    char* b = static_cast<char*>(workspace);
+    c->cfg = *cfg;
+    c->max_tokens = max_tokens;
+    c->esz = cfg->dtype == MOE_BF16 ? 2 : 4;
+    c->d_active_total = reinterpret_cast<unsigned long long*>(b + L.counters);
+    c->logits = reinterpret_cast<double*>(b + L.logits);
+    c->idx = reinterpret_cast<int32_t*>(b + L.idx);
+    c->w = reinterpret_cast<float*>(b + L.w);
+    c->counts = reinterpret_cast<int32_t*>(b + L.counts);
+    c->offsets = reinterpret_cast<int32_t*>(b + L.offsets);
+    c->perm = reinterpret_cast<int32_t*>(b + L.perm);
+    c->inv = reinterpret_cast<int32_t*>(b + L.inv);
+    c->tile_hist = reinterpret_cast<int32_t*>(b + L.tile_hist);
+    c->xa = b + L.xa;
+    c->xb = b + L.xb;
+    c->act = b + L.act;
+    c->y_perm = b + L.y_perm;
+    c->router_bytes = c->tokens_processed = 0;
+    c->iterations = c->layer_passes = 0;
+    if (hipMemsetAsync(b + L.counters, 0, 256, static_cast<hipStream_t>(stream)) != hipSuccess) {
+        delete c;
+        return MOE_ERR_DEVICE;
+    }
+    *out_ctx = c;
+    return MOE_OK;
+}
+
+moe_status moe_destroy(moe_ctx* ctx)
+{
+    if (!ctx) return MOE_ERR_NULL;
+    delete ctx;
+    return MOE_OK;
+}
+
+moe_status moe_router_topk(moe_ctx* ctx, const void* x, int64_t T, const void* w_router, const float* bias,
+                           int32_t* topk_idx, float* topk_w, void* stream)
+{
+    if (!ctx) return MOE_ERR_NULL;
+    if (T < 0 || T > ctx->max_tokens) return MOE_ERR_SHAPE;
+    if (T == 0) return MOE_OK;
+    if (!x || !w_router || !topk_idx || !topk_w) return MOE_ERR_NULL;
+    if (misaligned(x) || misaligned(w_router)) return MOE_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const moe_config& g = ctx->cfg;
+    hipError_t e = launch_router_logits(g.dtype, x, T, g.H, w_router, bias, g.E, ctx->logits, s);
+    if (e != hipSuccess) return MOE_ERR_DEVICE;
+    return dev(launch_topk(ctx->logits, T, g.E, g.K, g.renormalize, topk_idx, topk_w, s));
+}
+
+moe_status moe_permute(moe_ctx* ctx, const void* x, const int32_t* topk_idx, int64_t T, int32_t* counts,
+                       int32_t* offsets, int32_t* perm, int32_t* inv_perm, void* x_perm, void* stream)
+{
+    if (!ctx) return MOE_ERR_NULL;
+    if (T < 0 || T > ctx->max_tokens) return MOE_ERR_SHAPE;
+    if (!counts || !offsets) return MOE_ERR_NULL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const moe_config& g = ctx->cfg;
+    if (T == 0) {
+        if (hipMemsetAsync(counts, 0, sizeof(int32_t) * g.E, s) != hipSuccess) return MOE_ERR_DEVICE;
+        return dev(hipMemsetAsync(offsets, 0, sizeof(int32_t) * (g.E + 1), s));
+    }
+    if (!topk_idx || !perm || !inv_perm) return MOE_ERR_NULL;
+    if (x_perm && (!x || misaligned(x) || misaligned(x_perm))) return x ? MOE_ERR_ALIGN : MOE_ERR_NULL;
+    const int64_t A = T * g.K;
+    hipError_t e = launch_permute(topk_idx, A, g.E, counts, offsets, perm, inv_perm, ctx->tile_hist, nullptr, s);
+    if (e != hipSuccess) return MOE_ERR_DEVICE;
+    if (x_perm) return dev(launch_gather_rows(g.dtype, x, perm, g.K, A, g.H, x_perm, s));
+    return MOE_OK;
+}
+
+moe_status moe_grouped_ffn(moe_ctx* ctx, const void* x_perm, const int32_t* offsets, int64_t A,
+                           const void* w_gate_up, const void* w_down, void* y_perm, void* stream)
+{
+    if (!ctx) return MOE_ERR_NULL;
+    if (A < 0 || A > ctx->max_tokens * ctx->cfg.K) return MOE_ERR_SHAPE;
+    if (A == 0) return MOE_OK;
+    if (!x_perm || !offsets || !w_gate_up || !w_down || !y_perm) return MOE_ERR_NULL;
+    if (misaligned(x_perm) || misaligned(w_gate_up) || misaligned(w_down) || misaligned(y_perm)) return MOE_ERR_ALIGN;
+    const moe_config& g = ctx->cfg;
+    return dev(launch_grouped_ffn(g.dtype, x_perm, nullptr, 1, offsets, A, g.E, g.H, g.I, w_gate_up, w_down,
+                                  ctx->act, y_perm, static_cast<hipStream_t>(stream)));
+}
+
+moe_status moe_combine(moe_ctx* ctx, const void* y_perm, const int32_t* inv_perm, const float* topk_w,
+                       const void* residual, int64_t T, void* y, void* stream)
+{
+    if (!ctx) return MOE_ERR_NULL;
+    if (T < 0 || T > ctx->max_tokens) return MOE_ERR_SHAPE;
+    if (T == 0) return MOE_OK;
+    if (!y_perm || !inv_perm || !topk_w || !y) return MOE_ERR_NULL;
+    if (misaligned(y_perm) || misaligned(y) || (residual && misaligned(residual))) return MOE_ERR_ALIGN;
+    const moe_config& g = ctx->cfg;
+    return dev(launch_combine(g.dtype, y_perm, inv_perm, topk_w, residual, T, g.K, g.H, y, T, y,
+                              static_cast<hipStream_t>(stream)));
+}
+
+moe_status moe_group_forward(moe_ctx* ctx, const moe_layer* layers, int32_t n_layers, const void* x_decode,
+                             int64_t D, const void* x_prefill, int64_t P, moe_schedule sched, void* y_decode,
+                             void* y_prefill, void* stream)
+{
+    if (!ctx || !layers) return MOE_ERR_NULL;
+    if (n_layers <= 0 || D < 0 || P < 0) return MOE_ERR_SHAPE;
+    if (sched.kind != MOE_SCHED_CHUNKED && sched.kind != MOE_SCHED_LAYERED) return MOE_ERR_SCHEDULE;
+    if (sched.kind == MOE_SCHED_CHUNKED && sched.chunk <= 0) return MOE_ERR_SCHEDULE;
+    if (D + P == 0) return MOE_OK;
+    if ((D > 0 && (!x_decode || !y_decode)) || (P > 0 && (!x_prefill || !y_prefill))) return MOE_ERR_NULL;
+    if ((D > 0 && (misaligned(x_decode) || misaligned(y_decode))) ||
+        (P > 0 && (misaligned(x_prefill) || misaligned(y_prefill))))
+        return MOE_ERR_ALIGN;
+    for (int l = 0; l < n_layers; ++l) {
+        if (!layers[l].w_router || !layers[l].w_gate_up || !layers[l].w_down) return MOE_ERR_NULL;
+        if (misaligned(layers[l].w_router) || misaligned(layers[l].w_gate_up) || misaligned(layers[l].w_down))
+            return MOE_ERR_ALIGN;
+    }
+    const int64_t step = (sched.kind == MOE_SCHED_LAYERED || P == 0) ? (P > 0 ? P : 1) : (int64_t)sched.chunk;
+    const int64_t n_iter = (P == 0) ? 1 : (P + step - 1) / step;
+    if (D + (P < step ? P : step) > ctx->max_tokens) return MOE_ERR_SHAPE;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const moe_config& g = ctx->cfg;
+    const size_t row_bytes = (size_t)g.H * ctx->esz;
+    for (int64_t it = 0; it < n_iter; ++it) {
+        const int64_t p0 = it * step;
+        const int64_t pn = (P == 0) ? 0 : ((p0 + step <= P) ? step : P - p0);
+        const int64_t T = D + pn;
+        // hybrid batch: decode rows first, then this iteration's prefill rows
+        char* cur = static_cast<char*>(ctx->xa);
+        char* nxt = static_cast<char*>(ctx->xb);
+        if (D > 0 && hipMemcpyAsync(cur, x_decode, D * row_bytes, hipMemcpyDeviceToDevice, s) != hipSuccess)
+            return MOE_ERR_DEVICE;
+        if (pn > 0 && hipMemcpyAsync(cur + D * row_bytes, static_cast<const char*>(x_prefill) + p0 * row_bytes,
+                                     pn * row_bytes, hipMemcpyDeviceToDevice, s) != hipSuccess)
+            return MOE_ERR_DEVICE;
+        for (int l = 0; l < n_layers; ++l) {
+            moe_status st;
+            if (l + 1 < n_layers) {
+                st = run_layer(ctx, layers[l], cur, T, nxt, T, nxt, s);
+            } else {
+                void* yp = (P > 0) ? static_cast<char*>(y_prefill) + p0 * row_bytes : nullptr;
+                st = run_layer(ctx, layers[l], cur, T, y_decode, D, yp, s);
+            }
+            if (st != MOE_OK) return st;
+            char* t = cur; cur = nxt; nxt = t;
+            ctx->layer_passes += 1;
+            ctx->router_bytes += (uint64_t)g.E * g.H * ctx->esz;
+        }
+        ctx->iterations += 1;
+        ctx->tokens_processed += (uint64_t)T;
+    }
+    return MOE_OK;
+}
+
+moe_status moe_read_counters(moe_ctx* ctx, moe_counters* out, void* stream)
+{
+    if (!ctx || !out) return MOE_ERR_NULL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    unsigned long long active = 0;
+    if (hipMemcpyAsync(&active, ctx->d_active_total, sizeof(active), hipMemcpyDeviceToHost, s) != hipSuccess)
+        return MOE_ERR_DEVICE;
+    if (hipStreamSynchronize(s) != hipSuccess) return MOE_ERR_DEVICE;
+    const moe_config& g = ctx->cfg;
+    out->active_experts_total = active;
+    out->expert_bytes = (uint64_t)active * 3ull * (uint64_t)g.H * (uint64_t)g.I * (uint64_t)ctx->esz;
+    out->router_bytes = ctx->router_bytes;
+    out->tokens_processed = ctx->tokens_processed;
+    out->iterations = ctx->iterations;
+    out->layer_passes = ctx->layer_passes;
+    return MOE_OK;
+}
+
+moe_status moe_reset_counters(moe_ctx* ctx, void* stream)
+{
+    if (!ctx) return MOE_ERR_NULL;
+    ctx->router_bytes = ctx->tokens_processed = 0;
+    ctx->iterations = ctx->layer_passes = 0;
+    return dev(hipMemsetAsync(ctx->d_active_total, 0, sizeof(unsigned long long), static_cast<hipStream_t>(stream)));
+}
+
+const char* moe_ffn_variant(const moe_ctx* ctx, int64_t T)
+{
+    if (!ctx) return "";
+    const moe_config& g = ctx->cfg;
+    return ffn_variant_name(g.dtype, T * g.K, g.E, g.H, g.I);
+}
+
+const char* moe_status_string(moe_status s)
+{
+    switch (s) {
+        case MOE_OK: return "ok";
+        case MOE_ERR_NULL: return "null pointer";
+        case MOE_ERR_SHAPE: return "bad shape or size";
+        case MOE_ERR_DTYPE: return "unknown dtype";
+        case MOE_ERR_ALIGN: return "alignment (H, I multiples of 8; 16-byte aligned pointers)";
+        case MOE_ERR_WORKSPACE: return "workspace too small";
+        case MOE_ERR_SCHEDULE: return "bad schedule";
+        case MOE_ERR_DEVICE: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+}  // extern "C"

@@ -1,0 +1,71 @@
+// Shared device/host helpers for the gfx950 MoE kernels (not used by the CPU oracle).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "moe_lp.h"
+
+namespace moe {
+
+typedef uint16_t bf16_t;  // raw bfloat16 bit pattern
+
+constexpr int kWave = 64;
+constexpr int kMaxExperts = 512;
+constexpr int kMaxTopK = 64;
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// Round to nearest, ties to even (finite inputs; NaN stays NaN).
+__device__ __forceinline__ bf16_t f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+}
+
+template <typename T> struct elem;
+template <> struct elem<float> {
+    static __device__ __forceinline__ float to_f32(float v) { return v; }
+    static __device__ __forceinline__ float from_f32(float v) { return v; }
+};
+template <> struct elem<bf16_t> {
+    static __device__ __forceinline__ float to_f32(bf16_t v) { return bf16_to_f32(v); }
+    static __device__ __forceinline__ bf16_t from_f32(float v) { return f32_to_bf16(v); }
+};
+
+__device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & 63); }
+
+// ---- launchers implemented in the .hip files; all return hipError_t from hipGetLastError() ----
+
+// router.hip
+hipError_t launch_router_logits(int dtype, const void* x, int64_t T, int H, const void* w_router,
+                                const float* bias, int E, double* logits, hipStream_t s);
+hipError_t launch_topk(const double* logits, int64_t T, int E, int K, int renorm, int32_t* idx, float* w,
+                       hipStream_t s);
+
+// permute.hip
+constexpr int kPermTile = 8192;  // assignments per block of the permutation kernels
+hipError_t launch_permute(const int32_t* idx, int64_t A, int E, int32_t* counts, int32_t* offsets,
+                          int32_t* perm, int32_t* inv, int32_t* tile_hist, unsigned long long* active_total,
+                          hipStream_t s);
+hipError_t launch_gather_rows(int dtype, const void* x, const int32_t* perm, int K, int64_t A, int H,
+                              void* x_perm, hipStream_t s);
+
+// combine.hip
+hipError_t launch_combine(int dtype, const void* y_perm, const int32_t* inv, const float* w, const void* residual,
+                          int64_t T, int K, int H, void* y0, int64_t rows0, void* y1, hipStream_t s);
+
+// ffn.hip
+// x: [*, H]; row_map (or NULL): permuted row r reads x row row_map[r] / map_div; offsets [E+1].
+hipError_t launch_grouped_ffn(int dtype, const void* x, const int32_t* row_map, int map_div,
+                              const int32_t* offsets, int64_t A, int E, int H, int I, const void* w_gate_up,
+                              const void* w_down, void* act, void* y_perm, hipStream_t s);
+const char* ffn_variant_name(int dtype, int64_t A, int E, int H, int I);
+
+}  // namespace moe

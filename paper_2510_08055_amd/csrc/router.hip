@@ -1,0 +1,182 @@
+// Router: fp64 logits on the f64 matrix cores, then a wavefront-level top-k with
+// lowest-index tie-break and the softmax mixing weights (MoE router, Sec. 2.4).
+//
+// Logits are accumulated in fp64 so that the K selected experts and their order
+// agree with an fp64 definition: products of two bf16 (or two fp32) values are
+// exact in fp64 and the summation error (~1e-16 relative) is far below any
+// realistic gap between neighbouring logits.  The reduction order of a token's
+// logits depends only on H, never on the batch, so routing is batch-invariant:
+// the chunked and the layered schedule route every token identically.
+#include "common.h"
+
+namespace moe {
+
+typedef double double4_t __attribute__((ext_vector_type(4)));
+
+template <typename T> struct vec8;  // 8 consecutive elements widened to double
+template <> struct vec8<bf16_t> {
+    uint4 raw;
+    __device__ __forceinline__ void load(const bf16_t* p) { raw = *reinterpret_cast<const uint4*>(p); }
+    __device__ __forceinline__ void zero() { raw = make_uint4(0, 0, 0, 0); }
+    __device__ __forceinline__ double get(int j) const
+    {
+        const uint32_t w = (j < 2) ? raw.x : (j < 4) ? raw.y : (j < 6) ? raw.z : raw.w;
+        return (double)__uint_as_float((j & 1) ? (w & 0xffff0000u) : (w << 16));
+    }
+};
+template <> struct vec8<float> {
+    float4 a, b;
+    __device__ __forceinline__ void load(const float* p)
+    {
+        a = *reinterpret_cast<const float4*>(p);
+        b = *reinterpret_cast<const float4*>(p + 4);
+    }
+    __device__ __forceinline__ void zero() { a = b = make_float4(0.f, 0.f, 0.f, 0.f); }
+    __device__ __forceinline__ double get(int j) const
+    {
+        const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+        return (double)v[j];
+    }
+};
+
+// One wave: a 16-token x 16-expert tile of logits with v_mfma_f64_16x16x4.
+// Lane l supplies row (l % 16) of both operands; its quarter q = l / 16 owns the 8
+// consecutive k-values [c*32 + q*8, c*32 + q*8 + 8) of every 32-wide chunk c and feeds
+// them to 8 successive MFMAs (any fixed pairing of k-slots is a valid summation order).
+// Block = 4 waves = the same 16 tokens against 64 consecutive experts.
+template <typename T>
+__global__ __launch_bounds__(256) void router_logits_kernel(const T* __restrict__ x, int64_t n_tok, int H,
+                                                            const T* __restrict__ wr,
+                                                            const float* __restrict__ bias, int E,
+                                                            double* __restrict__ logits)
+{
+    const int lane = lane_id();
+    const int wave = threadIdx.x >> 6;
+    const int r = lane & 15, q = lane >> 4;
+    const int64_t t0 = (int64_t)blockIdx.x * 16;
+    const int e0 = (blockIdx.y * 4 + wave) * 16;
+    if (e0 >= E) return;
+    const int64_t tr = (t0 + r < n_tok) ? (t0 + r) : (n_tok - 1);  // clamp: loads stay in bounds
+    const int er = (e0 + r < E) ? (e0 + r) : (E - 1);
+    const T* xp = x + tr * (int64_t)H + q * 8;
+    const T* wp = wr + (int64_t)er * H + q * 8;
+
+    double4_t acc = {0.0, 0.0, 0.0, 0.0};
+    vec8<T> xa, wa;
+    for (int k0 = 0; k0 < H; k0 += 32) {
+        if (k0 + q * 8 < H) {
+            xa.load(xp + k0);
+            wa.load(wp + k0);
+        } else {
+            xa.zero();
+            wa.zero();
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc = __builtin_amdgcn_mfma_f64_16x16x4f64(xa.get(j), wa.get(j), acc, 0, 0, 0);
+    }
+    // D layout of the f64 16x16x4 MFMA: lane l, element v holds row 4*v + l/16 (token), column l % 16 (expert).
+    const int e = e0 + r;
+    if (e < E) {
+        const double b = bias ? (double)bias[e] : 0.0;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int64_t t = t0 + v * 4 + q;
+            if (t < n_tok) logits[t * E + e] = acc[v] + b;
+        }
+    }
+}
+
+// (value, index) "greater" under the routing order: larger logit first, equal logits by lower index.
+__device__ __forceinline__ bool before(double va, int ia, double vb, int ib)
+{
+    return va > vb || (va == vb && ia < ib);
+}
+
+// One wave per token.  Lane l holds logits of experts l, l+64, ...; K rounds of a wave-wide
+// arg-max, each removing the winner.  Lane j keeps the j-th winner and computes its weight.
+template <int NPL>
+__global__ __launch_bounds__(256) void topk_kernel(const double* __restrict__ logits, int64_t n_tok, int E, int K,
+                                                   int renorm, int32_t* __restrict__ idx, float* __restrict__ w)
+{
+    const int lane = lane_id();
+    const int64_t t = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (t >= n_tok) return;
+    const double NEG = -__builtin_huge_val();
+    double v[NPL];
+#pragma unroll
+    for (int i = 0; i < NPL; ++i) {
+        const int e = lane + 64 * i;
+        v[i] = (e < E) ? logits[t * E + e] : NEG;
+    }
+    double my_z = NEG;
+    int my_e = 0;
+    double z_max = 0.0;
+    for (int j = 0; j < K; ++j) {
+        double bv = v[0];
+        int bi = 0;
+#pragma unroll
+        for (int i = 1; i < NPL; ++i)
+            if (v[i] > bv) { bv = v[i]; bi = i; }
+        int be = lane + 64 * bi;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            const double ov = __shfl_xor(bv, off, 64);
+            const int oe = __shfl_xor(be, off, 64);
+            if (before(ov, oe, bv, be)) { bv = ov; be = oe; }
+        }
+        if (j == 0) z_max = bv;
+        if (lane == j) { my_z = bv; my_e = be; }
+        if ((be & 63) == lane) {
+            const int slot = be >> 6;
+#pragma unroll
+            for (int i = 0; i < NPL; ++i)
+                if (i == slot) v[i] = NEG;
+        }
+    }
+    // softmax numerator of the selected expert; denominator over all E unless renormalising
+    double p = (lane < K) ? exp(my_z - z_max) : 0.0;
+    double denom;
+    if (renorm) {
+        denom = p;
+    } else {
+        denom = 0.0;
+#pragma unroll
+        for (int i = 0; i < NPL; ++i) {
+            const int e = lane + 64 * i;
+            if (e < E) denom += exp(logits[t * E + e] - z_max);
+        }
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) denom += __shfl_xor(denom, off, 64);
+    if (lane < K) {
+        idx[t * K + lane] = my_e;
+        w[t * K + lane] = (float)(p / denom);
+    }
+}
+
+hipError_t launch_router_logits(int dtype, const void* x, int64_t T, int H, const void* w_router,
+                                const float* bias, int E, double* logits, hipStream_t s)
+{
+    dim3 grid((unsigned)((T + 15) / 16), (unsigned)((E + 63) / 64));
+    if (dtype == MOE_BF16)
+        router_logits_kernel<bf16_t><<<grid, 256, 0, s>>>((const bf16_t*)x, T, H, (const bf16_t*)w_router, bias, E,
+                                                          logits);
+    else
+        router_logits_kernel<float><<<grid, 256, 0, s>>>((const float*)x, T, H, (const float*)w_router, bias, E,
+                                                         logits);
+    return hipGetLastError();
+}
+
+hipError_t launch_topk(const double* logits, int64_t T, int E, int K, int renorm, int32_t* idx, float* w,
+                       hipStream_t s)
+{
+    const unsigned grid = (unsigned)((T + 3) / 4);
+    const int npl = (E + 63) / 64;
+    if (npl <= 1) topk_kernel<1><<<grid, 256, 0, s>>>(logits, T, E, K, renorm, idx, w);
+    else if (npl <= 2) topk_kernel<2><<<grid, 256, 0, s>>>(logits, T, E, K, renorm, idx, w);
+    else if (npl <= 4) topk_kernel<4><<<grid, 256, 0, s>>>(logits, T, E, K, renorm, idx, w);
+    else topk_kernel<8><<<grid, 256, 0, s>>>(logits, T, E, K, renorm, idx, w);
+    return hipGetLastError();
+}
+
+}  // namespace moe

@@ -1,0 +1,79 @@
+"""Host-side checks of the C ABI (no GPU needed): the library loads, exports every symbol the
+header declares, and rejects bad arguments with the documented status codes before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+import torch
+
+from paper_2510_08055_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "moe_lp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(moe_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = binding.load()
+    names = _declared()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_status_strings():
+    assert binding.status_string(0) == "ok"
+    assert len({binding.status_string(i) for i in range(8)}) == 8
+
+
+def _ws(H=256, E=8, K=2, I=512, dtype=1, T=64):
+    lib = binding.load()
+    cfg = binding.CConfig(H, E, K, I, dtype, 1, 1)
+    n = ctypes.c_size_t(0)
+    return lib.moe_workspace_bytes(ctypes.byref(cfg), T, ctypes.byref(n)), n.value
+
+
+def test_workspace_bytes_and_argument_errors():
+    st, n = _ws()
+    assert st == 0 and n > 0
+    st2, n2 = _ws(T=128)
+    assert st2 == 0 and n2 > n
+    # the big buffers are accounted for: act [T*K, I] and y_perm [T*K, H] in bf16
+    assert n >= 64 * 2 * (512 + 256) * 2
+    assert _ws(K=9)[0] == 2          # K > E            -> MOE_ERR_SHAPE
+    assert _ws(E=0)[0] == 2
+    assert _ws(E=4096)[0] == 2
+    assert _ws(T=0)[0] == 2
+    assert _ws(dtype=7)[0] == 3      # unknown dtype    -> MOE_ERR_DTYPE
+    assert _ws(H=257)[0] == 4        # H % 8 != 0       -> MOE_ERR_ALIGN
+    assert _ws(I=12)[0] == 4
+    lib = binding.load()
+    assert lib.moe_workspace_bytes(None, 64, ctypes.byref(ctypes.c_size_t(0))) == 1   # MOE_ERR_NULL
+    cfg = binding.CConfig(256, 8, 2, 512, 1, 1, 1)
+    assert lib.moe_workspace_bytes(ctypes.byref(cfg), 64, None) == 1
+
+
+def test_create_rejects_bad_arguments_before_touching_the_gpu():
+    lib = binding.load()
+    cfg = binding.CConfig(256, 8, 2, 512, 1, 1, 1)
+    ctx = ctypes.c_void_p()
+    fake = ctypes.c_void_p(0x10000)      # never dereferenced: every call below fails its checks first
+    assert lib.moe_create(ctypes.byref(cfg), 64, None, 1 << 30, None, ctypes.byref(ctx)) == 1
+    assert lib.moe_create(ctypes.byref(cfg), 64, fake, 16, None, ctypes.byref(ctx)) == 5          # workspace
+    assert lib.moe_create(ctypes.byref(cfg), 64, ctypes.c_void_p(0x10010), 1 << 30, None, ctypes.byref(ctx)) == 4
+    bad = binding.CConfig(256, 8, 9, 512, 1, 1, 1)
+    assert lib.moe_create(ctypes.byref(bad), 64, fake, 1 << 30, None, ctypes.byref(ctx)) == 2
+    assert lib.moe_destroy(None) == 1
+    assert lib.moe_router_topk(None, None, 4, None, None, None, None, None) == 1
+
+
+def test_binding_fails_loudly_without_the_library(monkeypatch):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", "/nonexistent/libmoe_lp.so")
+    with pytest.raises(RuntimeError):
+        binding.load()
