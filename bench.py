@@ -1,0 +1,158 @@
+#!/usr/bin/env python3
+"""Benchmark of the MoE expert-FFN hot path on one MI355X.
+
+A "step" is one pass of the whole path (router -> top-k -> permutation -> grouped gate_up/SwiGLU
+-> grouped down -> combine, for every layer and iteration of the chosen schedule) over one batch
+of seeded synthetic input that is already resident in HBM.  The default workload is the
+Qwen3-30B-A3B-shaped single MoE layer (64 decode tokens + one 2048-token prefill chunk, bf16).
+
+Prints ONE JSON line: tokens/s of the whole job, the roofline fraction of the dominant kernel
+(the gate_up grouped GEMM, timed live with HIP events on the launch stream), and the fp64 CPU
+oracle timed on this host's cores as a reported baseline.
+"""
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA
+BOUND = {"qwen3_layer": "hbm", "decode_large": "hbm", "qwen3_group8": None, "mixtral_zipf": "mfma", "tiny_f32": "hbm"}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="qwen3_layer")
+    ap.add_argument("--schedule", default="layered", choices=["layered", "chunked"])
+    ap.add_argument("--chunk", type=int, default=0, help="chunk size for --schedule chunked (default: the workload's)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def traffic_from_profiles(workload, schedule, variant):
+    """HBM bytes per gate_up launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE), if a
+    committed summary for this workload and kernel variant exists; else None."""
+    path = os.path.join(ROOT, "profiles", f"gate_up_traffic_{workload}_{schedule}.txt")
+    if not os.path.exists(path):
+        return None
+    text = open(path).read()
+    if f"variant: {variant}" not in text:
+        return None
+    m = re.search(r"traffic_bytes_per_launch:\s*([0-9.eE+]+)", text)
+    return float(m.group(1)) if m else None
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py measures the single-GPU hot path only: this build has no multi-GPU path "
+              "(run with --gpus 1; see DESIGN.md for how the path would shard)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2510_08055_amd import binding, inputs
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    w = inputs.WORKLOADS[args.workload]
+    chunk = args.chunk or w.chunk
+    dt = inputs.torch_dtype(w.dtype)
+    esz = 2 if w.dtype == "bf16" else 4
+
+    bias = None
+    layers = [inputs.make_layer(w, l, device=dev, router_bias=bias) for l in range(w.n_layers)]
+    xd, xp = inputs.make_hidden(w, device=dev)
+    T_iter = w.D + (w.P if args.schedule == "layered" else min(w.P, chunk))
+    ctx = binding.Context(w.H, w.E, w.K, w.I, dt, max_tokens=T_iter, residual=w.residual, device=dev)
+    packed = ctx.pack_layers(layers)
+    yd = torch.empty((w.D, w.H), dtype=dt, device=dev)
+    yp = torch.empty((w.P, w.H), dtype=dt, device=dev)
+
+    def step():
+        ctx.moe_group_forward(layers, xd if w.D else None, xp if w.P else None, args.schedule, chunk, packed=packed,
+                              y_decode=yd, y_prefill=yp)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ctx.moe_reset_counters()
+    ctx.moe_kernel_timing(["gate_up"])      # two event records per gate_up launch, on the launch stream
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    k_ms, k_n = ctx.moe_read_kernel_timing("gate_up")
+    ctr = ctx.moe_read_counters()
+    ctx.moe_kernel_timing([])
+
+    tokens_per_step = w.D + w.P                 # distinct tokens served by one step
+    ms_per_step = elapsed / args.steps * 1e3
+    value = tokens_per_step * args.steps / elapsed
+
+    # ---- roofline of the dominant kernel (gate_up grouped GEMM), per launch ----
+    launches_per_step = ctr.layer_passes / args.steps
+    active_per_launch = ctr.active_experts_total / ctr.layer_passes
+    rows_per_launch = ctr.tokens_processed / ctr.iterations            # batch rows T of one iteration (average)
+    A = rows_per_launch * w.K
+    alg_bytes = active_per_launch * 2 * w.I * w.H * esz + rows_per_launch * w.H * esz + A * w.I * esz
+    alg_flops = 2.0 * A * w.H * 2 * w.I
+    k_avg_s = k_ms / max(k_n, 1) * 1e-3
+    bound = BOUND.get(args.workload) or ("mfma" if args.schedule == "layered" else "hbm")
+    variant = ctx.moe_ffn_variant(int(rows_per_launch))
+    if bound == "hbm":
+        achieved, peak, unit = alg_bytes / k_avg_s / 1e9, HBM_PEAK_GBS, "GB/s"
+    else:
+        achieved, peak, unit = alg_flops / k_avg_s / 1e12, MFMA_BF16_PEAK_TFLOPS, "TFLOP/s"
+    roofline = {"bound": bound, "achieved": round(achieved, 2), "peak": peak, "unit": unit,
+                "frac": round(achieved / peak, 4), "traffic": traffic_from_profiles(args.workload, args.schedule, variant),
+                "kernel": variant, "kernel_avg_us": round(k_avg_s * 1e6, 2), "kernel_launches": k_n,
+                "algorithmic_bytes_per_launch": int(alg_bytes), "algorithmic_flops_per_launch": int(alg_flops)}
+
+    # ---- the oracle as it stands, on this host's cores, on a bounded sample of the same workload ----
+    cpu = None
+    if not args.no_cpu_baseline:
+        import numpy as np
+        import oracle
+        n_sample = min(tokens_per_step, 2112)
+        x = torch.cat([xd, xp])[:n_sample]
+        L0 = inputs.layer_to_numpy(layers[0])
+        xn = inputs.to_numpy(x)
+        t1 = time.perf_counter()
+        oracle.moe_layer(xn, L0["w_router"], L0["router_bias"], L0["w_gate_up"], L0["w_down"], w.K,
+                         residual=w.residual)
+        cpu_s = time.perf_counter() - t1
+        # one layer over n_sample tokens; a step crosses n_layers layers per token
+        cpu = {"value": round(n_sample / cpu_s / w.n_layers, 2), "unit": "tokens/s", "cores": oracle.num_threads(),
+               "kind": "oracle",
+               "sample": f"first {n_sample} rows of the batch through layer 0 (fp64 C, {cpu_s:.1f} s), "
+                         f"scaled by 1/{w.n_layers} layers"}
+
+    out = {
+        "metric": "MoE layer tokens/s", "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": args.workload, "schedule": args.schedule,
+                   "chunk": chunk if args.schedule == "chunked" else None, "H": w.H, "E": w.E, "top_k": w.K,
+                   "I": w.I, "layers": w.n_layers, "decode_tokens": w.D, "prefill_tokens": w.P, "seed": w.seed},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "expert_bytes_per_step": ctr.expert_bytes // args.steps,
+        "expert_bytes_per_prompt_token": (ctr.expert_bytes / args.steps / w.P) if w.P else None,
+        "iterations_per_step": ctr.iterations // args.steps,
+        "gate_up_launches_per_step": launches_per_step,
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -47,7 +47,7 @@ typedef enum { MOE_F32 = 0, MOE_BF16 = 1 } moe_dtype;
 /* Shape of one MoE layer (Table 3 gives E, K and H of the evaluated models). */
 typedef struct {
     int32_t H;           /* hidden size, multiple of 8 */
-    int32_t E;           /* number of experts, 1..1024 */
+    int32_t E;           /* number of experts, 1..512 */
     int32_t K;           /* experts per token (top-k), 1..min(E,64) */
     int32_t I;           /* expert intermediate size, multiple of 8 */
     int32_t dtype;       /* moe_dtype of activations and weights */
@@ -153,6 +153,21 @@ moe_status moe_group_forward(moe_ctx *ctx, const moe_layer *layers, int32_t n_la
 /* Copy the counters to host memory `out`; synchronises `stream`. */
 moe_status moe_read_counters(moe_ctx *ctx, moe_counters *out, void *stream);
 moe_status moe_reset_counters(moe_ctx *ctx, void *stream);
+
+/*
+ * Benchmark aid (not part of the method): bracket the launches of selected kernels inside
+ * moe_group_forward with HIP events on the caller's stream.  kernel_mask has bit (1 << id) set for
+ * every moe_kernel_id to time; 0 switches timing off.  Setting the mask discards earlier records.
+ * moe_read_kernel_timing synchronises `stream` and returns the summed duration (milliseconds) and
+ * the number of timed launches of one kernel since the mask was set.  (The permutation may be two
+ * launches; they are timed as one.)
+ */
+typedef enum {
+    MOE_KERNEL_ROUTER_LOGITS = 0, MOE_KERNEL_TOPK = 1, MOE_KERNEL_PERMUTE = 2,
+    MOE_KERNEL_GATE_UP = 3, MOE_KERNEL_DOWN = 4, MOE_KERNEL_COMBINE = 5, MOE_KERNEL_COUNT = 6
+} moe_kernel_id;
+moe_status moe_kernel_timing(moe_ctx *ctx, uint32_t kernel_mask);
+moe_status moe_read_kernel_timing(moe_ctx *ctx, int32_t kernel, double *total_ms, int64_t *launches, void *stream);
 
 /* Name of the gate_up GEMM kernel variant the context would use for a batch of T rows (host string,
  * static storage): lets a benchmark label its roofline line. */

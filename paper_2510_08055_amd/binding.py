@@ -20,7 +20,9 @@ MOE_SCHED_CHUNKED, MOE_SCHED_LAYERED = 0, 1
 
 EXPORTS = ["moe_workspace_bytes", "moe_create", "moe_destroy", "moe_router_topk", "moe_permute",
            "moe_grouped_ffn", "moe_combine", "moe_group_forward", "moe_read_counters", "moe_reset_counters",
-           "moe_ffn_variant", "moe_status_string"]
+           "moe_kernel_timing", "moe_read_kernel_timing", "moe_ffn_variant", "moe_status_string"]
+
+KERNELS = {"router_logits": 0, "topk": 1, "permute": 2, "gate_up": 3, "down": 4, "combine": 5}
 
 
 class MoeError(RuntimeError):
@@ -79,6 +81,8 @@ def load():
     L.moe_group_forward.argtypes = [vp, ctypes.POINTER(CLayer), i32, vp, i64, vp, i64, CSchedule, vp, vp, vp]
     L.moe_read_counters.argtypes = [vp, ctypes.POINTER(CCounters), vp]
     L.moe_reset_counters.argtypes = [vp, vp]
+    L.moe_kernel_timing.argtypes = [vp, ctypes.c_uint32]
+    L.moe_read_kernel_timing.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64), vp]
     L.moe_ffn_variant.argtypes = [vp, i64]
     L.moe_ffn_variant.restype = ctypes.c_char_p
     L.moe_status_string.argtypes = [i32]
@@ -226,6 +230,19 @@ class Context:
 
     def moe_reset_counters(self):
         _check(self.lib.moe_reset_counters(self._ctx, _stream()), "moe_reset_counters")
+
+    def moe_kernel_timing(self, kernels=()):
+        mask = 0
+        for k in kernels:
+            mask |= 1 << KERNELS[k]
+        _check(self.lib.moe_kernel_timing(self._ctx, mask), "moe_kernel_timing")
+
+    def moe_read_kernel_timing(self, kernel: str):
+        """(total milliseconds, launches) of one timed kernel since moe_kernel_timing was set."""
+        ms, n = ctypes.c_double(0), ctypes.c_int64(0)
+        _check(self.lib.moe_read_kernel_timing(self._ctx, KERNELS[kernel], ctypes.byref(ms), ctypes.byref(n),
+                                               _stream()), "moe_read_kernel_timing")
+        return ms.value, n.value
 
     def moe_ffn_variant(self, T: int) -> str:
         return self.lib.moe_ffn_variant(self._ctx, T).decode()

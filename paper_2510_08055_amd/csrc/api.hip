@@ -2,6 +2,8 @@
 // for the chunked (Sec. 2.3) and layered (Sec. 4.1-4.2) prefill schedules.  All arithmetic
 // happens in the kernels of router.hip / permute.hip / ffn.hip / combine.hip.
 #include <new>
+#include <utility>
+#include <vector>
 
 #include "common.h"
 
@@ -20,6 +22,9 @@ struct moe_ctx {
     // host-side counters (everything the host already knows)
     uint64_t router_bytes, tokens_processed;
     uint32_t iterations, layer_passes;
+    // benchmark aid: HIP event pairs around the launches of the kernels selected by timing_mask
+    uint32_t timing_mask;
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> timing[MOE_KERNEL_COUNT];
 };
 
 namespace {
@@ -66,6 +71,32 @@ Layout carve(const moe_config& c, int64_t Tm)
     return L;
 }
 
+// Records an event before and after one launch when that kernel is being timed.
+struct Timed {
+    moe_ctx* c; int id; hipStream_t s; bool on; hipEvent_t e0, e1;
+    Timed(moe_ctx* c_, int id_, hipStream_t s_) : c(c_), id(id_), s(s_), on(false), e0(nullptr), e1(nullptr)
+    {
+        if (!(c->timing_mask & (1u << id))) return;
+        if (hipEventCreate(&e0) != hipSuccess) return;
+        if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return; }
+        on = hipEventRecord(e0, s) == hipSuccess;
+    }
+    ~Timed()
+    {
+        if (!e1) return;
+        if (on && hipEventRecord(e1, s) == hipSuccess) c->timing[id].emplace_back(e0, e1);
+        else { (void)hipEventDestroy(e0); (void)hipEventDestroy(e1); }
+    }
+};
+
+void drop_timing(moe_ctx* c)
+{
+    for (auto& v : c->timing) {
+        for (auto& p : v) { (void)hipEventDestroy(p.first); (void)hipEventDestroy(p.second); }
+        v.clear();
+    }
+}
+
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 inline moe_status dev(hipError_t e) { return e == hipSuccess ? MOE_OK : MOE_ERR_DEVICE; }
 
@@ -75,17 +106,39 @@ moe_status run_layer(moe_ctx* c, const moe_layer& L, const void* x, int64_t T, v
 {
     const moe_config& g = c->cfg;
     const int64_t A = T * g.K;
-    hipError_t e = launch_router_logits(g.dtype, x, T, g.H, L.w_router, L.router_bias, g.E, c->logits, s);
+    hipError_t e;
+    {
+        Timed t(c, MOE_KERNEL_ROUTER_LOGITS, s);
+        e = launch_router_logits(g.dtype, x, T, g.H, L.w_router, L.router_bias, g.E, c->logits, s);
+    }
     if (e != hipSuccess) return MOE_ERR_DEVICE;
-    e = launch_topk(c->logits, T, g.E, g.K, g.renormalize, c->idx, c->w, s);
+    {
+        Timed t(c, MOE_KERNEL_TOPK, s);
+        e = launch_topk(c->logits, T, g.E, g.K, g.renormalize, c->idx, c->w, s);
+    }
     if (e != hipSuccess) return MOE_ERR_DEVICE;
-    e = launch_permute(c->idx, A, g.E, c->counts, c->offsets, c->perm, c->inv, c->tile_hist, c->d_active_total, s);
+    {
+        Timed t(c, MOE_KERNEL_PERMUTE, s);
+        e = launch_permute(c->idx, A, g.E, c->counts, c->offsets, c->perm, c->inv, c->tile_hist, c->d_active_total,
+                           s);
+    }
     if (e != hipSuccess) return MOE_ERR_DEVICE;
     // the activation rows are gathered inside the gate_up GEMM's tile loads: no x_perm round trip
-    e = launch_grouped_ffn(g.dtype, x, c->perm, g.K, c->offsets, A, g.E, g.H, g.I, L.w_gate_up, L.w_down, c->act,
-                           c->y_perm, s);
+    {
+        Timed t(c, MOE_KERNEL_GATE_UP, s);
+        e = launch_ffn_gate_up(g.dtype, x, c->perm, g.K, c->offsets, A, g.E, g.H, g.I, L.w_gate_up, c->act, s);
+    }
     if (e != hipSuccess) return MOE_ERR_DEVICE;
-    e = launch_combine(g.dtype, c->y_perm, c->inv, c->w, g.residual ? x : nullptr, T, g.K, g.H, y0, rows0, y1, s);
+    {
+        Timed t(c, MOE_KERNEL_DOWN, s);
+        e = launch_ffn_down(g.dtype, c->act, c->offsets, A, g.E, g.H, g.I, L.w_down, c->y_perm, s);
+    }
+    if (e != hipSuccess) return MOE_ERR_DEVICE;
+    {
+        Timed t(c, MOE_KERNEL_COMBINE, s);
+        e = launch_combine(g.dtype, c->y_perm, c->inv, c->w, g.residual ? x : nullptr, T, g.K, g.H, y0, rows0, y1,
+                           s);
+    }
     return dev(e);
 }
 
@@ -134,6 +187,7 @@ moe_status moe_create(const moe_config* cfg, int64_t max_tokens, void* workspace
     c->y_perm = b + L.y_perm;
     c->router_bytes = c->tokens_processed = 0;
     c->iterations = c->layer_passes = 0;
+    c->timing_mask = 0;
     if (hipMemsetAsync(b + L.counters, 0, 256, static_cast<hipStream_t>(stream)) != hipSuccess) {
         delete c;
         return MOE_ERR_DEVICE;
@@ -145,6 +199,7 @@ moe_status moe_create(const moe_config* cfg, int64_t max_tokens, void* workspace
 moe_status moe_destroy(moe_ctx* ctx)
 {
     if (!ctx) return MOE_ERR_NULL;
+    drop_timing(ctx);
     delete ctx;
     return MOE_OK;
 }
@@ -194,8 +249,10 @@ moe_status moe_grouped_ffn(moe_ctx* ctx, const void* x_perm, const int32_t* offs
     if (!x_perm || !offsets || !w_gate_up || !w_down || !y_perm) return MOE_ERR_NULL;
     if (misaligned(x_perm) || misaligned(w_gate_up) || misaligned(w_down) || misaligned(y_perm)) return MOE_ERR_ALIGN;
     const moe_config& g = ctx->cfg;
-    return dev(launch_grouped_ffn(g.dtype, x_perm, nullptr, 1, offsets, A, g.E, g.H, g.I, w_gate_up, w_down,
-                                  ctx->act, y_perm, static_cast<hipStream_t>(stream)));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = launch_ffn_gate_up(g.dtype, x_perm, nullptr, 1, offsets, A, g.E, g.H, g.I, w_gate_up, ctx->act, s);
+    if (e != hipSuccess) return MOE_ERR_DEVICE;
+    return dev(launch_ffn_down(g.dtype, ctx->act, offsets, A, g.E, g.H, g.I, w_down, y_perm, s));
 }
 
 moe_status moe_combine(moe_ctx* ctx, const void* y_perm, const int32_t* inv_perm, const float* topk_w,
@@ -291,6 +348,31 @@ moe_status moe_reset_counters(moe_ctx* ctx, void* stream)
     ctx->router_bytes = ctx->tokens_processed = 0;
     ctx->iterations = ctx->layer_passes = 0;
     return dev(hipMemsetAsync(ctx->d_active_total, 0, sizeof(unsigned long long), static_cast<hipStream_t>(stream)));
+}
+
+moe_status moe_kernel_timing(moe_ctx* ctx, uint32_t kernel_mask)
+{
+    if (!ctx) return MOE_ERR_NULL;
+    if (kernel_mask >> MOE_KERNEL_COUNT) return MOE_ERR_SHAPE;
+    drop_timing(ctx);
+    ctx->timing_mask = kernel_mask;
+    return MOE_OK;
+}
+
+moe_status moe_read_kernel_timing(moe_ctx* ctx, int32_t kernel, double* total_ms, int64_t* launches, void* stream)
+{
+    if (!ctx || !total_ms || !launches) return MOE_ERR_NULL;
+    if (kernel < 0 || kernel >= MOE_KERNEL_COUNT) return MOE_ERR_SHAPE;
+    if (hipStreamSynchronize(static_cast<hipStream_t>(stream)) != hipSuccess) return MOE_ERR_DEVICE;
+    double sum = 0.0;
+    for (auto& p : ctx->timing[kernel]) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, p.first, p.second) != hipSuccess) return MOE_ERR_DEVICE;
+        sum += ms;
+    }
+    *total_ms = sum;
+    *launches = (int64_t)ctx->timing[kernel].size();
+    return MOE_OK;
 }
 
 const char* moe_ffn_variant(const moe_ctx* ctx, int64_t T)

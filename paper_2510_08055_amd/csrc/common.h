@@ -63,9 +63,11 @@ hipError_t launch_combine(int dtype, const void* y_perm, const int32_t* inv, con
 
 // ffn.hip
 // x: [*, H]; row_map (or NULL): permuted row r reads x row row_map[r] / map_div; offsets [E+1].
-hipError_t launch_grouped_ffn(int dtype, const void* x, const int32_t* row_map, int map_div,
+hipError_t launch_ffn_gate_up(int dtype, const void* x, const int32_t* row_map, int map_div,
                               const int32_t* offsets, int64_t A, int E, int H, int I, const void* w_gate_up,
-                              const void* w_down, void* act, void* y_perm, hipStream_t s);
+                              void* act, hipStream_t s);
+hipError_t launch_ffn_down(int dtype, const void* act, const int32_t* offsets, int64_t A, int E, int H, int I,
+                           const void* w_down, void* y_perm, hipStream_t s);
 const char* ffn_variant_name(int dtype, int64_t A, int E, int H, int I);
 
 }  // namespace moe

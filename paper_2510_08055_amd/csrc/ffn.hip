@@ -294,27 +294,29 @@ static hipError_t launch_bf16(const bf16_t* X, int ldx, const int32_t* row_map, 
     return hipGetLastError();
 }
 
-hipError_t launch_grouped_ffn(int dtype, const void* x, const int32_t* row_map, int map_div, const int32_t* offsets,
-                              int64_t A, int E, int H, int I, const void* w_gate_up, const void* w_down, void* act,
-                              void* y_perm, hipStream_t s)
+hipError_t launch_ffn_gate_up(int dtype, const void* x, const int32_t* row_map, int map_div, const int32_t* offsets,
+                              int64_t A, int E, int H, int I, const void* w_gate_up, void* act, hipStream_t s)
 {
-    if (dtype == MOE_BF16) {
-        hipError_t e = launch_bf16<128, 128, true>((const bf16_t*)x, H, row_map, map_div, offsets, E, A,
-                                                   (const bf16_t*)w_gate_up, (int64_t)2 * I * H, I, H, (bf16_t*)act,
-                                                   I, s);
-        if (e != hipSuccess) return e;
+    if (dtype == MOE_BF16)
+        return launch_bf16<128, 128, true>((const bf16_t*)x, H, row_map, map_div, offsets, E, A,
+                                           (const bf16_t*)w_gate_up, (int64_t)2 * I * H, I, H, (bf16_t*)act, I, s);
+    const unsigned grid = (unsigned)((A * I + 255) / 256);
+    grouped_gemm_f32_kernel<true><<<grid, 256, 0, s>>>((const float*)x, H, row_map, map_div, offsets, E,
+                                                       (const float*)w_gate_up, (int64_t)2 * I * H, I, H, A,
+                                                       (float*)act, I);
+    return hipGetLastError();
+}
+
+hipError_t launch_ffn_down(int dtype, const void* act, const int32_t* offsets, int64_t A, int E, int H, int I,
+                           const void* w_down, void* y_perm, hipStream_t s)
+{
+    if (dtype == MOE_BF16)
         return launch_bf16<128, 128, false>((const bf16_t*)act, I, nullptr, 1, offsets, E, A, (const bf16_t*)w_down,
                                             (int64_t)H * I, H, I, (bf16_t*)y_perm, H, s);
-    }
-    const unsigned g1 = (unsigned)((A * I + 255) / 256), g2 = (unsigned)((A * H + 255) / 256);
-    grouped_gemm_f32_kernel<true><<<g1, 256, 0, s>>>((const float*)x, H, row_map, map_div, offsets, E,
-                                                     (const float*)w_gate_up, (int64_t)2 * I * H, I, H, A,
-                                                     (float*)act, I);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    grouped_gemm_f32_kernel<false><<<g2, 256, 0, s>>>((const float*)act, I, nullptr, 1, offsets, E,
-                                                      (const float*)w_down, (int64_t)H * I, H, I, A, (float*)y_perm,
-                                                      H);
+    const unsigned grid = (unsigned)((A * H + 255) / 256);
+    grouped_gemm_f32_kernel<false><<<grid, 256, 0, s>>>((const float*)act, I, nullptr, 1, offsets, E,
+                                                        (const float*)w_down, (int64_t)H * I, H, I, A,
+                                                        (float*)y_perm, H);
     return hipGetLastError();
 }
 
