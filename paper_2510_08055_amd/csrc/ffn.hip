@@ -5,6 +5,11 @@
 //
 // Both operands are K-contiguous (activations [rows,K], weights [N,K]), which is exactly
 // the MFMA operand layout: each lane feeds 8 consecutive k-values of one row.
+#include <stdlib.h>
+#include <string.h>
+
+#include <type_traits>
+
 #include "common.h"
 
 namespace moe {
@@ -28,10 +33,13 @@ constexpr int kLdsStride = 72; // bf16 elements per LDS row: 64 + 8 pad -> 144 B
 // expert's activation rows stay in the same L2 while its n-tiles stream by.
 // ----------------------------------------------------------------------------------------------
 struct TileCoord {
-    int expert, row0, row_end, n_tile;
+    int expert, row0, row_end, n_tile;   // rows [row0, row_end) of the permuted batch belong to this tile
     bool valid;
 };
 
+// An expert with m rows is cut into ceil(m / BM) m-tiles of (nearly) equal size, each a whole number of
+// 32-row blocks: 1032 rows and BM = 256 give 224+224+224+192+168 rather than 4 x 256 + 8, so no block
+// streams a whole weight tile for a handful of rows.
 __device__ __forceinline__ TileCoord find_tile(const int32_t* __restrict__ offsets, int E, int BM, int n_tiles)
 {
     constexpr int EPL = kMaxExperts / 64;
@@ -75,8 +83,14 @@ __device__ __forceinline__ TileCoord find_tile(const int32_t* __restrict__ offse
         if (rem >= 0 && rem < cnt) {
             expert = lane * EPL + i;
             n_tile = (int)(rem / mt[i]);
-            row0 = off[i] + (int)(rem % mt[i]) * BM;
-            row_end = off[i + 1];
+            const int t = (int)(rem % mt[i]);
+            const int m = off[i + 1] - off[i];
+            const int rb = (m + 31) / 32;                       // 32-row blocks of this expert
+            const int per = (rb + mt[i] - 1) / mt[i];           // row blocks per tile
+            row0 = off[i] + t * per * 32;
+            row_end = row0 + per * 32;
+            if (row_end > off[i + 1]) row_end = off[i + 1];
+            if (row0 > row_end) row0 = row_end;                 // cannot happen: per * (mt - 1) < rb
             rem = -1;
         } else if (rem >= 0) {
             rem -= cnt;
@@ -231,6 +245,270 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16_kernel(
     }
 }
 
+
+// ----------------------------------------------------------------------------------------------
+// Pipelined grouped GEMM: global -> LDS copies issued as direct-to-LDS loads
+// (global_load_lds_dwordx4: no staging registers, no LDS store instructions), NSTAGE stages of
+// PBK (64 or 32) k-values in flight, one barrier per stage.  Used for both regimes of Sec. 2.5:
+//   - weight streaming (few rows per expert): WM = 1, the 4 waves split the weight rows, each wave
+//     multiplies all RBM row blocks; deep staging keeps >= 64 KB of loads in flight per CU.
+//   - compute bound (hundreds of rows per expert): WM = 2, 2x2 waves with large wave tiles so that
+//     LDS operand traffic per MFMA stays low.
+// One wave-level load moves 64 lanes x 16 B = 8 (or 16) whole tile rows into 1 KB of LDS.  LDS rows
+// are unpadded (the hardware writes lanes contiguously), so bank conflicts on the 16-byte operand
+// reads are avoided by an XOR swizzle applied on the SOURCE side: LDS chunk c of tile row r holds
+// global 16-byte chunk c ^ swz(r).
+// Row blocks (32 rows) of the m-tile that hold no real row are skipped by every wave.
+// The k-order of the MFMAs is the same as in the other variants (bit-identical results).
+// Requires K % PBK == 0.
+// ----------------------------------------------------------------------------------------------
+typedef __attribute__((address_space(3))) void lds_ptr_t;
+typedef __attribute__((address_space(1))) const void glb_ptr_t;
+
+// Waits and barriers of the software pipeline are inline asm with a memory clobber: the compiler must
+// not move LDS reads or the direct-to-LDS loads across them (the bare s_barrier intrinsic is not a
+// memory barrier for the optimiser, and __syncthreads() would drain every load still in flight).
+template <int N> __device__ __forceinline__ void wait_vmcnt()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+__device__ __forceinline__ void wait_lds_reads() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+__device__ __forceinline__ void block_barrier() { asm volatile("s_barrier" ::: "memory"); }
+
+// Source-side swizzle of a tile row: which LDS 16-byte chunk slot holds global chunk c of row r is
+// c ^ swz(r).  Chosen so that the 16-byte operand reads of 8 (and of 16) consecutive rows fall into
+// distinct bank groups whether the LDS serves 128 or 256 bytes per clock.
+template <int PBK> __device__ __forceinline__ int swz(int r)
+{
+    if (PBK == 64) return (r & 7) ^ ((r >> 3) & 1);
+    return ((r >> 1) & 3) ^ ((r >> 3) & 1);
+}
+
+template <int RBM, int BN, int WM, int NSTAGE, int PBK, int MINW, bool GATED>
+__global__ __launch_bounds__(256, MINW) void grouped_gemm_bf16_pipe_kernel(
+    const bf16_t* __restrict__ X, int ldx, const int32_t* __restrict__ row_map, int map_div,
+    const int32_t* __restrict__ offsets, int E, const bf16_t* __restrict__ W, int64_t w_expert_stride, int N, int K,
+    bf16_t* __restrict__ Out, int ldo)
+{
+    constexpr int BM = RBM * 32, WN = 4 / WM;
+    constexpr int NO = GATED ? BN / 2 : BN;     // output columns per block
+    constexpr int TM = RBM / WM;                // row blocks per wave: rb = wm + WM * i
+    constexpr int WNO = NO / WN;                // output columns per wave
+    constexpr int TNO = WNO / 32;
+    constexpr int TN = GATED ? 2 * TNO : TNO;
+    constexpr int ROWB = PBK * 2;                       // bytes per LDS tile row
+    constexpr int CPR = PBK / 8;                        // 16-byte chunks per row
+    constexpr int RPL = 64 / CPR;                       // tile rows moved by one wave-level load (1 KB)
+    constexpr int KS = PBK / 16;                        // MFMA k-slices per stage
+    constexpr int A_LPW = BM / RPL / 4, B_LPW = BN / RPL / 4;   // load groups per wave and stage
+    constexpr int LPS = A_LPW + B_LPW;                  // load instructions per thread and stage
+    constexpr int STAGE = (BM + BN) * ROWB;             // bytes
+    static_assert(PBK == 64 || PBK == 32, "stage depth must be 64 or 32");
+    static_assert(RBM % WM == 0 && TM <= 4 && TNO >= 1 && (NSTAGE - 2) * LPS < 64, "bad tile configuration");
+    static_assert(BM % (RPL * 4) == 0 && BN % (RPL * 4) == 0, "tile rows must split evenly over the four waves");
+    constexpr int WAIT_MAIN = (NSTAGE - 2) * LPS;   // loads younger than the stage waited for
+    static_assert(WAIT_MAIN < 64, "vmcnt is a 6-bit counter");
+
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+
+    const int n_tiles = (N + NO - 1) / NO;
+    const TileCoord tc = find_tile(offsets, E, BM, n_tiles);
+    if (!tc.valid) return;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int n0 = tc.n_tile * NO;
+    const bf16_t* We = W + (int64_t)tc.expert * w_expert_stride;
+    const int rows_here = (tc.row_end - tc.row0) < BM ? (tc.row_end - tc.row0) : BM;
+    const int rb_valid = (rows_here + 31) / 32;   // row blocks of this tile with at least one real row
+
+    // ---- source addresses of this lane's loads: group g = wave + 4*p covers tile rows RPL*g .. RPL*g + RPL-1 ----
+    const int l_row = lane / CPR, l_chunk = lane % CPR;
+    const bf16_t* a_src[A_LPW];
+    const bf16_t* b_src[B_LPW];
+#pragma unroll
+    for (int p = 0; p < A_LPW; ++p) {
+        const int tr = (wave + 4 * p) * RPL + l_row;      // row inside the tile
+        int r = tc.row0 + tr;
+        if (r >= tc.row_end) r = tc.row_end - 1;
+        const int64_t src = row_map ? (int64_t)(row_map[r] / map_div) : (int64_t)r;
+        a_src[p] = X + src * ldx + ((l_chunk ^ swz<PBK>(tr)) << 3);
+    }
+#pragma unroll
+    for (int p = 0; p < B_LPW; ++p) {
+        const int rb = (wave + 4 * p) * RPL + l_row;
+        int n;
+        if (GATED) n = (rb < NO) ? (n0 + rb) : (n0 + rb - NO);
+        else n = n0 + rb;
+        if (n >= N) n = N - 1;
+        if (GATED && rb >= NO) n += N;
+        b_src[p] = We + (int64_t)n * K + ((l_chunk ^ swz<PBK>(rb)) << 3);
+    }
+    // Load `part` (of KS) of stage kt into LDS buffer buf: the loads of a stage are spread over the
+    // k-slices of the stage being multiplied, so that they issue in the shadow of the MFMAs.
+    auto issue_part = [&](int kt, int buf, int part) {
+        char* base = smem + buf * STAGE;
+        const int k0 = kt * PBK;
+#pragma unroll
+        for (int p = 0; p < LPS; ++p) {
+            if (p % KS != part) continue;
+            if (p < A_LPW)
+                __builtin_amdgcn_global_load_lds((glb_ptr_t*)(a_src[p] + k0),
+                                                 (lds_ptr_t*)(base + (wave + 4 * p) * 1024), 16, 0, 0);
+            else
+                __builtin_amdgcn_global_load_lds((glb_ptr_t*)(b_src[p - A_LPW] + k0),
+                                                 (lds_ptr_t*)(base + BM * ROWB + (wave + 4 * (p - A_LPW)) * 1024), 16,
+                                                 0, 0);
+        }
+    };
+    auto issue_stage = [&](int kt, int buf) {
+#pragma unroll
+        for (int part = 0; part < KS; ++part) issue_part(kt, buf, part);
+    };
+    // ---- LDS byte offsets of the operand rows this lane feeds to the MFMAs ----
+    const int fr = lane & 31, fq = lane >> 5;
+    const int fsw = swz<PBK>(fr);     // the swizzle only looks at the low 4 row bits; row blocks are 32 rows
+    int a_row[TM], b_row[TN], k_off[KS];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) a_row[i] = ((wm + WM * i) * 32 + fr) * ROWB;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        int r;
+        if (GATED) r = (j < TNO) ? (wn * WNO + j * 32 + fr) : (NO + wn * WNO + (j - TNO) * 32 + fr);
+        else r = wn * WNO + j * 32 + fr;
+        b_row[j] = BM * ROWB + r * ROWB;
+    }
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) k_off[kk] = ((kk * 2 + fq) ^ fsw) << 4;
+
+    const int nk_ = K / PBK;
+    // Software pipeline.  Global side: stages kt+1 .. kt+NSTAGE-1 are in flight while stage kt is
+    // multiplied.  LDS side: the operand fragments of k-slice kk+1 are read while the MFMAs of slice
+    // kk run; the last slice of a stage runs after the barrier that hands over the next stage, under
+    // the reads of that stage's first slice.
+    // The body is instantiated for the number TMV of row blocks this wave really has (0..TM), so the
+    // hot loop is straight-line code; a wave with no row block still loads and synchronises.
+    auto run = [&](auto tmv_const) {
+        constexpr int TMV = decltype(tmv_const)::value;
+        constexpr int TMA = TMV > 0 ? TMV : 1;
+        float16_t acc[TMA][TN];
+#pragma unroll
+        for (int i = 0; i < TMA; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+        bf16x8_t af[2][TMA], bfr[2][TN];
+        auto read_frags = [&](const char* base, int kk, int set) {
+            if (TMV == 0) return;
+#pragma unroll
+            for (int i = 0; i < TMV; ++i)
+                af[set][i] = *reinterpret_cast<const bf16x8_t*>(base + a_row[i] + k_off[kk]);
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                bfr[set][j] = *reinterpret_cast<const bf16x8_t*>(base + b_row[j] + k_off[kk]);
+        };
+        auto mfma_set = [&](int set) {
+#pragma unroll
+            for (int i = 0; i < TMV; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[set][i], bfr[set][j], acc[i][j], 0, 0, 0);
+        };
+
+#pragma unroll
+        for (int st = 0; st < NSTAGE - 1; ++st)
+            if (st < nk_) issue_stage(st, st);
+        if (nk_ >= NSTAGE - 1) wait_vmcnt<WAIT_MAIN>();
+        else wait_vmcnt<0>();
+        block_barrier();
+        read_frags(smem, 0, 0);
+        // One k-step.  MORE: stage kt+NSTAGE-1 exists and is loaded (in KS parts, between the MFMAs)
+        // into the buffer stage kt-1 used, free since the last barrier.  NEXT: stage kt+1 exists; it is
+        // waited for and handed over by the barrier before the last slice of this stage is multiplied.
+        // Ask the scheduler to issue the LDS reads and the global loads of a region one by one between
+        // its MFMAs (they then execute in the shadow of the matrix pipe) instead of in a clump.
+        auto interleave = [](int n_ds, int n_vmem, int n_mfma) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                if (i < n_ds && i < n_mfma) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                if (i < n_vmem && n_ds + i < n_mfma) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // one global load
+                }
+            }
+        };
+        auto parts_in = [](int part) {
+            int n = 0;
+            for (int p = 0; p < LPS; ++p) n += (p % KS == part);
+            return n;
+        };
+        auto step = [&](int kt, auto more_c, auto next_c, auto drain_c) {
+            constexpr bool MORE = decltype(more_c)::value, NEXT = decltype(next_c)::value;
+            constexpr bool DRAIN = decltype(drain_c)::value;
+            const char* base = smem + (kt % NSTAGE) * STAGE;
+            const int nxt = kt + NSTAGE - 1;
+            const int nxt_buf = nxt % NSTAGE;
+#pragma unroll
+            for (int kk = 0; kk < KS - 1; ++kk) {
+                read_frags(base, kk + 1, (kk + 1) & 1);
+                if (MORE) issue_part(nxt, nxt_buf, kk);
+                mfma_set(kk & 1);
+                interleave(TMV > 0 ? TMV + TN : 0, MORE ? parts_in(kk) : 0, TMV * TN);
+            }
+            if (MORE) issue_part(nxt, nxt_buf, KS - 1);
+            if (NEXT) {
+                if (DRAIN) wait_vmcnt<0>();
+                else wait_vmcnt<WAIT_MAIN>();
+                // all of this wave's reads of stage kt have returned before its buffer may be refilled
+                wait_lds_reads();
+                block_barrier();
+                read_frags(smem + ((kt + 1) % NSTAGE) * STAGE, 0, 0);
+            }
+            mfma_set((KS - 1) & 1);
+            interleave(NEXT && TMV > 0 ? TMV + TN : 0, 0, TMV * TN);
+        };
+        using T = std::true_type;
+        using F = std::false_type;
+        const int n_main = nk_ - (NSTAGE - 1) > 0 ? nk_ - (NSTAGE - 1) : 0;   // steps that still start a new stage
+        int kt = 0;
+        for (; kt < n_main; ++kt) step(kt, T{}, T{}, F{});
+        for (; kt < nk_ - 1; ++kt) step(kt, F{}, T{}, T{});     // pipeline drains: wait for everything
+        step(kt, F{}, F{}, F{});
+
+#pragma unroll
+        for (int i = 0; i < TMV; ++i) {
+#pragma unroll
+            for (int j = 0; j < TNO; ++j) {
+                const int col = n0 + wn * WNO + j * 32 + fr;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int row = tc.row0 + (wm + WM * i) * 32 + (v >> 2) * 8 + fq * 4 + (v & 3);
+                    float val;
+                    if (GATED) val = silu_mul(acc[i][j][v], acc[i][j + TNO][v]);
+                    else val = acc[i][j][v];
+                    if (row < tc.row_end && col < N) Out[(int64_t)row * ldo + col] = f32_to_bf16(val);
+                }
+            }
+        }
+    };
+
+    // row blocks wm, wm + WM, ... below rb_valid belong to this wave
+    const int tm_valid = (rb_valid - wm + WM - 1) / WM;
+    if (TM >= 4 && tm_valid >= 4) run(std::integral_constant<int, (TM >= 4 ? 4 : 0)>{});
+    else if (TM >= 3 && tm_valid >= 3) run(std::integral_constant<int, (TM >= 3 ? 3 : 0)>{});
+    else if (TM >= 2 && tm_valid >= 2) run(std::integral_constant<int, (TM >= 2 ? 2 : 0)>{});
+    else if (tm_valid >= 1) run(std::integral_constant<int, 1>{});
+    else run(std::integral_constant<int, 0>{});
+}
+
 // ----------------------------------------------------------------------------------------------
 // fp32 reference-precision path (small correctness workloads): one thread per output element.
 // ----------------------------------------------------------------------------------------------
@@ -271,8 +549,30 @@ __global__ __launch_bounds__(256) void grouped_gemm_f32_kernel(const float* __re
 }
 
 // ----------------------------------------------------------------------------------------------
+// Host side: variant choice and launches.  The host never sees the per-expert counts (they live on
+// the device), so the variant is chosen from the mean rows per expert A/E; every variant is correct
+// for any distribution of rows.
+// ----------------------------------------------------------------------------------------------
+enum Variant { V_TILE128 = 0, V_PIPE_S2, V_PIPE_B8 };
+
+static Variant pick_variant(int64_t A, int E, int K)
+{
+    static const char* force = getenv("MOE_FFN_VARIANT");   // tuning aid: "tile128", "pipe_s2", "pipe_b8"
+    Variant v;
+    const double mean_rows = (double)A / (double)E;
+    if (mean_rows <= 64.0) v = V_PIPE_S2;      // weight streaming: 64-row tiles, 4 waves across the weight rows
+    else v = V_PIPE_B8;                        // up to 256-row tiles, 2x2 waves of 128x128
+    if (force) {
+        if (!strcmp(force, "tile128")) v = V_TILE128;
+        if (!strcmp(force, "pipe_s2")) v = V_PIPE_S2;
+        if (!strcmp(force, "pipe_b8")) v = V_PIPE_B8;
+    }
+    if (K % 64 != 0) v = V_TILE128;            // the pipelined kernels have no k-tail path
+    return v;
+}
+
 template <int BM, int BN, bool GATED>
-static hipError_t launch_bf16(const bf16_t* X, int ldx, const int32_t* row_map, int map_div, const int32_t* offsets,
+static hipError_t launch_tile(const bf16_t* X, int ldx, const int32_t* row_map, int map_div, const int32_t* offsets,
                               int E, int64_t A, const bf16_t* W, int64_t w_expert_stride, int N, int K, bf16_t* Out,
                               int ldo, hipStream_t s)
 {
@@ -294,12 +594,52 @@ static hipError_t launch_bf16(const bf16_t* X, int ldx, const int32_t* row_map, 
     return hipGetLastError();
 }
 
+template <int RBM, int BN, int WM, int NSTAGE, int PBK, int MINW, bool GATED>
+static hipError_t launch_pipe(const bf16_t* X, int ldx, const int32_t* row_map, int map_div, const int32_t* offsets,
+                              int E, int64_t A, const bf16_t* W, int64_t w_expert_stride, int N, int K, bf16_t* Out,
+                              int ldo, hipStream_t s)
+{
+    constexpr int BM = RBM * 32;
+    constexpr int NO = GATED ? BN / 2 : BN;
+    const size_t lds_bytes = (size_t)NSTAGE * (BM + BN) * PBK * 2;
+    auto kern = grouped_gemm_bf16_pipe_kernel<RBM, BN, WM, NSTAGE, PBK, MINW, GATED>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int64_t n_tiles = (N + NO - 1) / NO;
+    const int64_t m_tiles_max = (A + BM - 1) / BM + (A < E ? A : E);
+    const int64_t grid = ((m_tiles_max * n_tiles + 7) / 8) * 8;
+    kern<<<(unsigned)grid, 256, lds_bytes, s>>>(X, ldx, row_map, map_div, offsets, E, W, w_expert_stride, N, K, Out,
+                                                ldo);
+    return hipGetLastError();
+}
+
+template <bool GATED>
+static hipError_t launch_bf16(const bf16_t* X, int ldx, const int32_t* row_map, int map_div, const int32_t* offsets,
+                              int E, int64_t A, const bf16_t* W, int64_t w_expert_stride, int N, int K, bf16_t* Out,
+                              int ldo, hipStream_t s)
+{
+    switch (pick_variant(A, E, K)) {
+        case V_PIPE_S2:
+            return launch_pipe<2, 256, 1, 3, 64, 1, GATED>(X, ldx, row_map, map_div, offsets, E, A, W, w_expert_stride, N, K, Out, ldo, s);
+        case V_PIPE_B8:
+            return launch_pipe<8, 256, 2, 4, 32, 1, GATED>(X, ldx, row_map, map_div, offsets, E, A, W, w_expert_stride, N, K, Out, ldo, s);
+        default:
+            return launch_tile<128, 128, GATED>(X, ldx, row_map, map_div, offsets, E, A, W, w_expert_stride, N, K, Out,
+                                                ldo, s);
+    }
+}
+
 hipError_t launch_ffn_gate_up(int dtype, const void* x, const int32_t* row_map, int map_div, const int32_t* offsets,
                               int64_t A, int E, int H, int I, const void* w_gate_up, void* act, hipStream_t s)
 {
     if (dtype == MOE_BF16)
-        return launch_bf16<128, 128, true>((const bf16_t*)x, H, row_map, map_div, offsets, E, A,
-                                           (const bf16_t*)w_gate_up, (int64_t)2 * I * H, I, H, (bf16_t*)act, I, s);
+        return launch_bf16<true>((const bf16_t*)x, H, row_map, map_div, offsets, E, A, (const bf16_t*)w_gate_up,
+                                 (int64_t)2 * I * H, I, H, (bf16_t*)act, I, s);
     const unsigned grid = (unsigned)((A * I + 255) / 256);
     grouped_gemm_f32_kernel<true><<<grid, 256, 0, s>>>((const float*)x, H, row_map, map_div, offsets, E,
                                                        (const float*)w_gate_up, (int64_t)2 * I * H, I, H, A,
@@ -311,8 +651,8 @@ hipError_t launch_ffn_down(int dtype, const void* act, const int32_t* offsets, i
                            const void* w_down, void* y_perm, hipStream_t s)
 {
     if (dtype == MOE_BF16)
-        return launch_bf16<128, 128, false>((const bf16_t*)act, I, nullptr, 1, offsets, E, A, (const bf16_t*)w_down,
-                                            (int64_t)H * I, H, I, (bf16_t*)y_perm, H, s);
+        return launch_bf16<false>((const bf16_t*)act, I, nullptr, 1, offsets, E, A, (const bf16_t*)w_down,
+                                  (int64_t)H * I, H, I, (bf16_t*)y_perm, H, s);
     const unsigned grid = (unsigned)((A * H + 255) / 256);
     grouped_gemm_f32_kernel<false><<<grid, 256, 0, s>>>((const float*)act, I, nullptr, 1, offsets, E,
                                                         (const float*)w_down, (int64_t)H * I, H, I, A,
@@ -322,8 +662,13 @@ hipError_t launch_ffn_down(int dtype, const void* act, const int32_t* offsets, i
 
 const char* ffn_variant_name(int dtype, int64_t A, int E, int H, int I)
 {
-    (void)A; (void)E; (void)H; (void)I;
-    return dtype == MOE_BF16 ? "grouped_gemm_bf16_kernel<128,128,gated>" : "grouped_gemm_f32_kernel<gated>";
+    (void)I;
+    if (dtype != MOE_BF16) return "grouped_gemm_f32_kernel<gated>";
+    switch (pick_variant(A, E, H)) {
+        case V_PIPE_S2: return "grouped_gemm_bf16_pipe_kernel<2,256,1,3,64,gated>";
+        case V_PIPE_B8: return "grouped_gemm_bf16_pipe_kernel<8,256,2,4,32,gated>";
+        default: return "grouped_gemm_bf16_kernel<128,128,gated>";
+    }
 }
 
 }  // namespace moe

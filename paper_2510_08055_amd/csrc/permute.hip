@@ -117,27 +117,34 @@ __global__ __launch_bounds__(kPermThreads) void permute_scatter_kernel(
     while ((1 << nbits) < E) ++nbits;
     int my_e[kPermRounds], my_rank[kPermRounds];
     const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+    // all of this thread's expert ids are fetched up front: one memory latency, not one per round
 #pragma unroll
     for (int r = 0; r < kPermRounds; ++r) {
         const int64_t f = base + (int64_t)wave * (kPermRounds * 64) + r * 64 + lane;
-        const bool valid = f < A;
-        const int e = valid ? clamp_expert(idx[f], E) : 0;
+        my_e[r] = (f < A) ? clamp_expert(idx[f], E) : -1;
+    }
+#pragma unroll
+    for (int r = 0; r < kPermRounds; ++r) {
+        const bool valid = my_e[r] >= 0;
+        const int e = valid ? my_e[r] : 0;
         uint64_t peers = __ballot(valid);
         for (int b = 0; b < nbits; ++b) {
             const bool bit = (e >> b) & 1;
             const uint64_t bal = __ballot(valid && bit);
             peers &= bit ? bal : ~bal;
         }
-        my_e[r] = valid ? e : -1;
         if (valid) {
             my_rank[r] = wave_cnt[wave][e] + __popcll(peers & lt_mask);
         } else {
             my_rank[r] = 0;
         }
-        __syncthreads();   // everyone has read the running counter of this round
+        // wave_cnt[wave] is private to this wave and a wave's LDS operations execute in program order,
+        // so the update below cannot overtake the reads above: no block barrier inside the rounds.
+        __builtin_amdgcn_wave_barrier();
         if (valid && (63 - __clzll(peers)) == lane) wave_cnt[wave][e] += __popcll(peers);
-        __syncthreads();
+        __builtin_amdgcn_wave_barrier();
     }
+    __syncthreads();   // the scatter below adds the counts of the waves in front of this one
 #pragma unroll
     for (int r = 0; r < kPermRounds; ++r) {
         const int e = my_e[r];

@@ -39,23 +39,24 @@ template <> struct vec8<float> {
     }
 };
 
-// One wave: a 16-token x 16-expert tile of logits with v_mfma_f64_16x16x4.
-// Lane l supplies row (l % 16) of both operands; its quarter q = l / 16 owns the 8
-// consecutive k-values [c*32 + q*8, c*32 + q*8 + 8) of every 32-wide chunk c and feeds
-// them to 8 successive MFMAs (any fixed pairing of k-slots is a valid summation order).
-// Block = 4 waves = the same 16 tokens against 64 consecutive experts.
+// One block: a 16-token x 16-expert tile of logits with v_mfma_f64_16x16x4; its 4 waves split the
+// hidden dimension (wave w takes the 32-wide k-chunks w, w+4, w+8, ...) and their partial tiles are
+// added in wave order 0,1,2,3 through LDS, so the summation order of a logit is fixed by H alone.
+// Lane l supplies row (l % 16) of both operands; its quarter q = l / 16 owns the 8 consecutive
+// k-values [c*32 + q*8, c*32 + q*8 + 8) of chunk c and feeds them to 8 successive MFMAs (any fixed
+// pairing of k-slots is a valid summation order).  Many short waves per SIMD hide the load latency.
 template <typename T>
 __global__ __launch_bounds__(256) void router_logits_kernel(const T* __restrict__ x, int64_t n_tok, int H,
                                                             const T* __restrict__ wr,
                                                             const float* __restrict__ bias, int E,
                                                             double* __restrict__ logits)
 {
+    __shared__ double part[3][4][64];   // partial tiles of waves 1..3: [wave-1][element v][lane]
     const int lane = lane_id();
     const int wave = threadIdx.x >> 6;
     const int r = lane & 15, q = lane >> 4;
     const int64_t t0 = (int64_t)blockIdx.x * 16;
-    const int e0 = (blockIdx.y * 4 + wave) * 16;
-    if (e0 >= E) return;
+    const int e0 = blockIdx.y * 16;
     const int64_t tr = (t0 + r < n_tok) ? (t0 + r) : (n_tok - 1);  // clamp: loads stay in bounds
     const int er = (e0 + r < E) ? (e0 + r) : (E - 1);
     const T* xp = x + tr * (int64_t)H + q * 8;
@@ -63,7 +64,7 @@ __global__ __launch_bounds__(256) void router_logits_kernel(const T* __restrict_
 
     double4_t acc = {0.0, 0.0, 0.0, 0.0};
     vec8<T> xa, wa;
-    for (int k0 = 0; k0 < H; k0 += 32) {
+    for (int k0 = wave * 32; k0 < H; k0 += 128) {
         if (k0 + q * 8 < H) {
             xa.load(xp + k0);
             wa.load(wp + k0);
@@ -74,6 +75,12 @@ __global__ __launch_bounds__(256) void router_logits_kernel(const T* __restrict_
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc = __builtin_amdgcn_mfma_f64_16x16x4f64(xa.get(j), wa.get(j), acc, 0, 0, 0);
     }
+    if (wave > 0) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) part[wave - 1][v][lane] = acc[v];
+    }
+    __syncthreads();
+    if (wave != 0) return;
     // D layout of the f64 16x16x4 MFMA: lane l, element v holds row 4*v + l/16 (token), column l % 16 (expert).
     const int e = e0 + r;
     if (e < E) {
@@ -81,7 +88,8 @@ __global__ __launch_bounds__(256) void router_logits_kernel(const T* __restrict_
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             const int64_t t = t0 + v * 4 + q;
-            if (t < n_tok) logits[t * E + e] = acc[v] + b;
+            const double z = ((acc[v] + part[0][v][lane]) + part[1][v][lane]) + part[2][v][lane];
+            if (t < n_tok) logits[t * E + e] = z + b;
         }
     }
 }
@@ -157,7 +165,7 @@ __global__ __launch_bounds__(256) void topk_kernel(const double* __restrict__ lo
 hipError_t launch_router_logits(int dtype, const void* x, int64_t T, int H, const void* w_router,
                                 const float* bias, int E, double* logits, hipStream_t s)
 {
-    dim3 grid((unsigned)((T + 15) / 16), (unsigned)((E + 63) / 64));
+    dim3 grid((unsigned)((T + 15) / 16), (unsigned)((E + 15) / 16));
     if (dtype == MOE_BF16)
         router_logits_kernel<bf16_t><<<grid, 256, 0, s>>>((const bf16_t*)x, T, H, (const bf16_t*)w_router, bias, E,
                                                           logits);

@@ -100,6 +100,9 @@ def test_permute_bit_exact(gpu_lib, T, K, E):
     (256, 512, 4, [130, 0, 1, 64], "bf16"),       # an empty expert, a 1-row expert, a ragged tile
     (256, 512, 3, [5, 200, 33], "f32"),
     (192, 72, 2, [257, 31], "bf16"),              # N and K tails: I = 72, H = 192
+    (256, 320, 5, [3, 0, 70, 1, 33], "bf16"),     # mean 21 rows/expert: streaming variant, one 32-row block per pass
+    (2880, 2880, 3, [8, 5, 11], "bf16"),          # decode-like: H = I = 2880 (tails in N), 8 rows per expert
+    (256, 328, 5, [40, 64, 65, 0, 100], "bf16"),  # mean 54 rows/expert: streaming variant, two row blocks per pass
 ])
 def test_grouped_ffn_is_the_dense_swiglu_of_each_expert(gpu_lib, H, I, E, rows, dtype):
     A = sum(rows)
@@ -255,6 +258,25 @@ def test_group_forward_edge_cases(gpu_lib):
         small.moe_group_forward(layers, xd, xp, "layered")
     assert e.value.status == 2
     small.moe_group_forward(layers, xd, xp, "chunked", 16)        # fits: 9 + 16 rows per iteration
+
+
+def test_decode_heavy_layer_full_width_sampled(gpu_lib):
+    # the decode-heavy workload's layer shape (H = I = 2880, E = 128, top-4, 256 tokens, ~8 rows per expert)
+    w = inputs.scaled(inputs.WORKLOADS["decode_large"], n_layers=1)
+    L = inputs.make_layer(w, 0, device=DEV)
+    xd, _ = inputs.make_hidden(w, device=DEV)
+    ctx = make_ctx(gpu_lib, w, w.D)
+    yd, _ = ctx.moe_group_forward([L], xd, None, "layered")
+    idx, wt = ctx.moe_router_topk(xd, L["w_router"])
+    Ln = inputs.layer_to_numpy(L)
+    xn = inputs.to_numpy(xd)
+    o_idx, o_w, gap = oracle.router_topk(xn, Ln["w_router"], None, w.K, want_gap=True)
+    assert gap.min() > 1e-9 and (idx.cpu().numpy() == o_idx).all()
+    rows = np.arange(0, w.D, 11)
+    o_y, _, _ = oracle.moe_layer(xn[rows], Ln["w_router"], None, Ln["w_gate_up"], Ln["w_down"], w.K, residual=True)
+    assert_close(yd[torch.from_numpy(rows).to(DEV)], o_y, "bf16", "decode-heavy layer (sampled rows)")
+    c = ctx.moe_read_counters()
+    assert c.active_experts_total == len(set(o_idx.reshape(-1).tolist()))
 
 
 # --------------------------------------------------- full benchmark shape, sampled outputs
