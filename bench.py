@@ -67,8 +67,7 @@ def main():
     dt = inputs.torch_dtype(w.dtype)
     esz = 2 if w.dtype == "bf16" else 4
 
-    bias = None
-    layers = [inputs.make_layer(w, l, device=dev, router_bias=bias) for l in range(w.n_layers)]
+    layers = [inputs.make_layer(w, l, device=dev) for l in range(w.n_layers)]
     xd, xp = inputs.make_hidden(w, device=dev)
     T_iter = w.D + (w.P if args.schedule == "layered" else min(w.P, chunk))
     ctx = binding.Context(w.H, w.E, w.K, w.I, dt, max_tokens=T_iter, residual=w.residual, device=dev)

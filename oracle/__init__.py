@@ -129,10 +129,11 @@ def permute(idx, E):
     return counts, offsets, perm, inv
 
 
-def moe_layer(x, w_router, bias, w_gate_up, w_down, k, renormalize=True, residual=False):
+def moe_layer(x, w_router, bias, w_gate_up, w_down, k, renormalize=True, residual=False, want_mag=False):
     """One MoE layer.  x [T,H]; w_router [E,H]; w_gate_up [E,2I,H]; w_down [E,H,I].
 
-    Returns y [T,H] f64 (unrounded), idx [T,k] int32, w [T,k] f64.
+    Returns y [T,H] f64 (unrounded), idx [T,k] int32, w [T,k] f64 (and, with want_mag, y_mag [T,H] =
+    sum_j w_j |expert output| (+ |x|): the magnitude of the terms y is summed from).
     """
     x, w_router, w_gate_up, w_down = _c(x), _c(w_router), _c(w_gate_up), _c(w_down)
     T, H = x.shape
@@ -145,10 +146,13 @@ def moe_layer(x, w_router, bias, w_gate_up, w_down, k, renormalize=True, residua
     y = np.zeros((T, H), dtype=np.float64)
     idx = np.zeros((T, k), dtype=np.int32)
     w = np.zeros((T, k), dtype=np.float64)
+    mag = np.zeros((T, H), dtype=np.float64) if want_mag else None
     rc = lib().orc_moe_layer(_p(x), _dt(x), ctypes.c_int64(T), ctypes.c_int64(H), _p(w_router), _p(b),
                              _p(w_gate_up), _p(w_down), wdt, E, k, ctypes.c_int64(I),
-                             int(bool(renormalize)), int(bool(residual)), _p(y), _p(idx), _p(w))
+                             int(bool(renormalize)), int(bool(residual)), _p(y), _p(idx), _p(w), _p(mag))
     _check(rc, "moe_layer")
+    if want_mag:
+        return y, idx, w, mag
     return y, idx, w
 
 

@@ -233,11 +233,13 @@ static void expert_token(const double *xt, int64_t H, int64_t I, const void *Wgu
  *   x [T,H] (xdt); Wr [E,H], Wgu [E,2I,H], Wd [E,H,I] (all wdt); bias [E] fp32 or NULL
  *   y [T,H] f64 = sum_j w[t,j] * expert_{idx[t,j]}(x_t)  (+ x_t when residual != 0)
  *   idx [T,k], w [T,k] f64 are also returned (either may be NULL).
+ *   y_mag [T,H] (optional): sum_j w[t,j] * |expert output| (+ |x_t|), the magnitude of the terms y is
+ *   made of; a caller uses it to size the rounding budget of a reduced-precision implementation.
  */
 int orc_moe_layer(const void *x, int xdt, int64_t T, int64_t H,
                   const void *Wr, const float *bias, const void *Wgu, const void *Wd, int wdt,
                   int E, int k, int64_t I, int renorm, int residual,
-                  double *y, int32_t *idx_out, double *w_out)
+                  double *y, int32_t *idx_out, double *w_out, double *y_mag)
 {
     if (T < 0 || H <= 0 || I <= 0 || E <= 0 || k <= 0 || k > E) return ORC_ERR_ARG;
     int status = ORC_OK;
@@ -259,12 +261,16 @@ int orc_moe_layer(const void *x, int xdt, int64_t T, int64_t H,
                 continue;
             }
             double *yt = y + t * H;
+            double *mt = y_mag ? y_mag + t * H : NULL;
             for (int64_t h = 0; h < H; ++h) yt[h] = 0.0;
+            if (mt) for (int64_t h = 0; h < H; ++h) mt[h] = 0.0;
             for (int j = 0; j < k; ++j) {
                 expert_token(xt, H, I, Wgu, Wd, wdt, idx[j], a, o);
                 for (int64_t h = 0; h < H; ++h) yt[h] += w[j] * o[h];
+                if (mt) for (int64_t h = 0; h < H; ++h) mt[h] += w[j] * fabs(o[h]);
             }
             if (residual) for (int64_t h = 0; h < H; ++h) yt[h] += xt[h];
+            if (residual && mt) for (int64_t h = 0; h < H; ++h) mt[h] += fabs(xt[h]);
             if (idx_out) memcpy(idx_out + t * k, idx, sizeof(int32_t) * (size_t)k);
             if (w_out) memcpy(w_out + t * k, w, sizeof(double) * (size_t)k);
         }
@@ -340,7 +346,7 @@ int orc_group_forward(const void *const *Wr, const float *const *bias,
         for (int64_t i = 0; i < pn * H; ++i) xb[D * H + i] = ld(x_prefill, xdt, p0 * H + i);
         for (int l = 0; l < n_layers; ++l) {
             status = orc_moe_layer(xb, ORC_F64, T, H, Wr[l], (bias && bias[l]) ? bias[l] : NULL,
-                                   Wgu[l], Wd[l], wdt, E, k, I, renorm, residual, yb, idx, NULL);
+                                   Wgu[l], Wd[l], wdt, E, k, I, renorm, residual, yb, idx, NULL, NULL);
             if (status != ORC_OK) break;
             if (idx_trace) {
                 memcpy(idx_trace + trace_pos, idx, sizeof(int32_t) * (size_t)(T * k));

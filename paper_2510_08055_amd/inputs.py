@@ -14,6 +14,8 @@ then rounded ONCE to the workload dtype; every consumer sees those exact bits.
 Tensors can be drawn on the CPU or directly on the GPU (large weights); the two
 devices give different, individually reproducible, streams.
 """
+import json
+import os
 import zlib
 from dataclasses import dataclass, replace
 from typing import Optional
@@ -88,20 +90,41 @@ def zipf_shares(E: int, s: float) -> np.ndarray:
     return p / p.sum()
 
 
-def make_layer(w: Workload, layer: int, device: str = "cpu", router_bias: Optional[torch.Tensor] = None):
-    """Random weights of one MoE layer: dict of w_router [E,H], router_bias, w_gate_up [E,2I,H], w_down [E,H,I]."""
+def stored_router_bias(w: Workload, layer: int) -> Optional[torch.Tensor]:
+    """Per-expert router bias of a skewed-routing workload (fp32 [E], CPU), or None.
+
+    The values were calibrated once, against the CPU-drawn router weights and hidden states of the
+    workload, so that the experts' assignment shares follow Zipf(zipf_s); they are stored as data in
+    data/router_bias_<workload>.json (written by oracle/calibrate_zipf_bias.py).
+    """
+    if w.zipf_s <= 0:
+        return None
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "data", f"router_bias_{w.name}.json")
+    with open(path) as f:
+        rec = json.load(f)
+    assert rec["E"] == w.E and rec["seed"] == w.seed and abs(rec["zipf_s"] - w.zipf_s) < 1e-12
+    return torch.tensor(rec["bias"][layer], dtype=torch.float32)
+
+
+def make_layer(w: Workload, layer: int, device: str = "cpu", with_bias: bool = True):
+    """Random weights of one MoE layer: dict of w_router [E,H], router_bias, w_gate_up [E,2I,H], w_down [E,H,I].
+
+    The (small) router tensors are always drawn on the CPU, so that they are the same bits wherever the
+    (large) expert weights are drawn; everything is returned on `device`.
+    """
+    bias = stored_router_bias(w, layer) if with_bias else None
     return {
-        "w_router": randn((w.E, w.H), 0.02, w.seed, "w_router", layer, w.dtype, device),
-        "router_bias": router_bias,
+        "w_router": randn((w.E, w.H), 0.02, w.seed, "w_router", layer, w.dtype, "cpu").to(device),
+        "router_bias": None if bias is None else bias.to(device),
         "w_gate_up": randn((w.E, 2 * w.I, w.H), 0.02, w.seed, "w_gate_up", layer, w.dtype, device),
         "w_down": randn((w.E, w.H, w.I), 0.02, w.seed, "w_down", layer, w.dtype, device),
     }
 
 
 def make_hidden(w: Workload, device: str = "cpu"):
-    """(x_decode [D,H], x_prefill [P,H]) ~ N(0,1)."""
-    xd = randn((w.D, w.H), 1.0, w.seed, "x_decode", 0, w.dtype, device)
-    xp = randn((w.P, w.H), 1.0, w.seed, "x_prefill", 0, w.dtype, device)
+    """(x_decode [D,H], x_prefill [P,H]) ~ N(0,1); drawn on the CPU (same bits everywhere), returned on `device`."""
+    xd = randn((w.D, w.H), 1.0, w.seed, "x_decode", 0, w.dtype, "cpu").to(device)
+    xp = randn((w.P, w.H), 1.0, w.seed, "x_prefill", 0, w.dtype, "cpu").to(device)
     return xd, xp
 
 

@@ -124,6 +124,21 @@ def test_equivariances():
     np.testing.assert_allclose(yE, dense, rtol=1e-12, atol=1e-14)
 
 
+def test_magnitude_output_is_the_weighted_abs_sum():
+    rng = np.random.default_rng(16)
+    T, H, I, E, k = 6, 9, 5, 4, 2
+    wr, wgu, wd = _rand_layer(rng, E, H, I)
+    x = rng.standard_normal((T, H))
+    y, idx, w, mag = oracle.moe_layer(x, wr, None, wgu, wd, k, residual=True, want_mag=True)
+    ref = np.abs(x).copy()
+    for t in range(T):
+        for j in range(k):
+            e = idx[t, j]
+            ref[t] += w[t, j] * np.abs(_dense_swiglu(x[t:t + 1], wgu[e, :I], wgu[e, I:], wd[e])[0])
+    np.testing.assert_allclose(mag, ref, rtol=1e-12)
+    assert (mag >= np.abs(y) - 1e-12).all()          # triangle inequality
+
+
 def test_layer_routing_agrees_with_router_call():
     rng = np.random.default_rng(14)
     wr, wgu, wd = _rand_layer(rng, 8, 16, 8)
@@ -267,3 +282,18 @@ def test_iid_coverage_curve_matches_expectation():
             cov.append(len(set(idx.reshape(-1).tolist())) / E)
         expect = 1 - (1 - k / E) ** B
         assert abs(np.mean(cov) - expect) < 0.04
+
+
+def test_stored_zipf_bias_gives_zipf_shares():
+    # Mixtral-shaped workload: the stored router bias makes the experts' assignment shares follow Zipf(1.2)
+    w = inputs.WORKLOADS["mixtral_zipf"]
+    xd, xp = inputs.make_hidden(w)
+    x = inputs.to_numpy(torch.cat([xd, xp]))
+    wr = inputs.to_numpy(inputs.randn((w.E, w.H), 0.02, w.seed, "w_router", 0, w.dtype, "cpu"))
+    b = inputs.stored_router_bias(w, 0).numpy()
+    idx, wt = oracle.router_topk(x, wr, b, w.K)
+    share = np.bincount(idx.reshape(-1), minlength=w.E) / idx.size
+    target = inputs.zipf_shares(w.E, w.zipf_s)
+    assert np.abs(share - target).max() < 2e-3
+    assert abs(target[0] - 0.4286) < 1e-3 and abs(target[-1] - 0.0353) < 1e-3     # Zipf(1.2) over 8 experts
+    np.testing.assert_allclose(wt.sum(1), 1.0, rtol=1e-13)
