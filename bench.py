@@ -34,6 +34,9 @@ def parse_args():
     ap.add_argument("--schedule", default="layered", choices=["layered", "chunked"])
     ap.add_argument("--chunk", type=int, default=0, help="chunk size for --schedule chunked (default: the workload's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 1 GiB device-to-device copy kernel a few times (reference for scaling "
+                         "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run) and exit")
     return ap.parse_args()
 
 
@@ -62,6 +65,15 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
+    if args.copy_calibration:
+        n = 1 << 30
+        src = torch.ones(n, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_read": n, "copy_calibration_bytes_written": n, "launches": 5}))
+        return
     w = inputs.WORKLOADS[args.workload]
     chunk = args.chunk or w.chunk
     dt = inputs.torch_dtype(w.dtype)
