@@ -101,26 +101,30 @@ inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) &
 inline moe_status dev(hipError_t e) { return e == hipSuccess ? MOE_OK : MOE_ERR_DEVICE; }
 
 // One layer on the batch `x` [T,H]; output rows [0,rows0) -> y0, the rest -> y1.
-moe_status run_layer(moe_ctx* c, const moe_layer& L, const void* x, int64_t T, void* y0, int64_t rows0, void* y1,
+moe_status run_layer(moe_ctx* c, const moe_layer& L, RowSrc x, int64_t T, void* y0, int64_t rows0, void* y1,
                      hipStream_t s)
 {
     const moe_config& g = c->cfg;
     const int64_t A = T * g.K;
+    // with more than one permutation tile the top-k kernel counts the per-tile expert histograms itself
+    const int n_perm_tiles = (int)((A + kPermTile - 1) / kPermTile);
+    const bool fused_hist = n_perm_tiles > 1;
     hipError_t e;
     {
         Timed t(c, MOE_KERNEL_ROUTER_LOGITS, s);
-        e = launch_router_logits(g.dtype, x, T, g.H, L.w_router, L.router_bias, g.E, c->logits, s);
+        e = launch_router_logits(g.dtype, x, T, g.H, L.w_router, L.router_bias, g.E, c->logits, c->tile_hist,
+                                 fused_hist ? n_perm_tiles * g.E : 0, s);
     }
     if (e != hipSuccess) return MOE_ERR_DEVICE;
     {
         Timed t(c, MOE_KERNEL_TOPK, s);
-        e = launch_topk(c->logits, T, g.E, g.K, g.renormalize, c->idx, c->w, s);
+        e = launch_topk(c->logits, T, g.E, g.K, g.renormalize, c->idx, c->w, fused_hist ? c->tile_hist : nullptr, s);
     }
     if (e != hipSuccess) return MOE_ERR_DEVICE;
     {
         Timed t(c, MOE_KERNEL_PERMUTE, s);
-        e = launch_permute(c->idx, A, g.E, c->counts, c->offsets, c->perm, c->inv, c->tile_hist, c->d_active_total,
-                           s);
+        e = launch_permute(c->idx, A, g.E, c->counts, c->offsets, c->perm, c->inv, c->tile_hist, fused_hist,
+                           c->d_active_total, s);
     }
     if (e != hipSuccess) return MOE_ERR_DEVICE;
     // the activation rows are gathered inside the gate_up GEMM's tile loads: no x_perm round trip
@@ -136,8 +140,7 @@ moe_status run_layer(moe_ctx* c, const moe_layer& L, const void* x, int64_t T, v
     if (e != hipSuccess) return MOE_ERR_DEVICE;
     {
         Timed t(c, MOE_KERNEL_COMBINE, s);
-        e = launch_combine(g.dtype, c->y_perm, c->inv, c->w, g.residual ? x : nullptr, T, g.K, g.H, y0, rows0, y1,
-                           s);
+        e = launch_combine(g.dtype, c->y_perm, c->inv, c->w, g.residual != 0, x, T, g.K, g.H, y0, rows0, y1, s);
     }
     return dev(e);
 }
@@ -214,9 +217,9 @@ moe_status moe_router_topk(moe_ctx* ctx, const void* x, int64_t T, const void* w
     if (misaligned(x) || misaligned(w_router)) return MOE_ERR_ALIGN;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const moe_config& g = ctx->cfg;
-    hipError_t e = launch_router_logits(g.dtype, x, T, g.H, w_router, bias, g.E, ctx->logits, s);
+    hipError_t e = launch_router_logits(g.dtype, single_src(x), T, g.H, w_router, bias, g.E, ctx->logits, nullptr, 0, s);
     if (e != hipSuccess) return MOE_ERR_DEVICE;
-    return dev(launch_topk(ctx->logits, T, g.E, g.K, g.renormalize, topk_idx, topk_w, s));
+    return dev(launch_topk(ctx->logits, T, g.E, g.K, g.renormalize, topk_idx, topk_w, nullptr, s));
 }
 
 moe_status moe_permute(moe_ctx* ctx, const void* x, const int32_t* topk_idx, int64_t T, int32_t* counts,
@@ -234,7 +237,7 @@ moe_status moe_permute(moe_ctx* ctx, const void* x, const int32_t* topk_idx, int
     if (!topk_idx || !perm || !inv_perm) return MOE_ERR_NULL;
     if (x_perm && (!x || misaligned(x) || misaligned(x_perm))) return x ? MOE_ERR_ALIGN : MOE_ERR_NULL;
     const int64_t A = T * g.K;
-    hipError_t e = launch_permute(topk_idx, A, g.E, counts, offsets, perm, inv_perm, ctx->tile_hist, nullptr, s);
+    hipError_t e = launch_permute(topk_idx, A, g.E, counts, offsets, perm, inv_perm, ctx->tile_hist, false, nullptr, s);
     if (e != hipSuccess) return MOE_ERR_DEVICE;
     if (x_perm) return dev(launch_gather_rows(g.dtype, x, perm, g.K, A, g.H, x_perm, s));
     return MOE_OK;
@@ -250,7 +253,8 @@ moe_status moe_grouped_ffn(moe_ctx* ctx, const void* x_perm, const int32_t* offs
     if (misaligned(x_perm) || misaligned(w_gate_up) || misaligned(w_down) || misaligned(y_perm)) return MOE_ERR_ALIGN;
     const moe_config& g = ctx->cfg;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    hipError_t e = launch_ffn_gate_up(g.dtype, x_perm, nullptr, 1, offsets, A, g.E, g.H, g.I, w_gate_up, ctx->act, s);
+    hipError_t e = launch_ffn_gate_up(g.dtype, single_src(x_perm), nullptr, 1, offsets, A, g.E, g.H, g.I, w_gate_up,
+                                      ctx->act, s);
     if (e != hipSuccess) return MOE_ERR_DEVICE;
     return dev(launch_ffn_down(g.dtype, ctx->act, offsets, A, g.E, g.H, g.I, w_down, y_perm, s));
 }
@@ -264,8 +268,8 @@ moe_status moe_combine(moe_ctx* ctx, const void* y_perm, const int32_t* inv_perm
     if (!y_perm || !inv_perm || !topk_w || !y) return MOE_ERR_NULL;
     if (misaligned(y_perm) || misaligned(y) || (residual && misaligned(residual))) return MOE_ERR_ALIGN;
     const moe_config& g = ctx->cfg;
-    return dev(launch_combine(g.dtype, y_perm, inv_perm, topk_w, residual, T, g.K, g.H, y, T, y,
-                              static_cast<hipStream_t>(stream)));
+    return dev(launch_combine(g.dtype, y_perm, inv_perm, topk_w, residual != nullptr, single_src(residual), T, g.K,
+                              g.H, y, T, y, static_cast<hipStream_t>(stream)));
 }
 
 moe_status moe_group_forward(moe_ctx* ctx, const moe_layer* layers, int32_t n_layers, const void* x_decode,
@@ -297,21 +301,19 @@ moe_status moe_group_forward(moe_ctx* ctx, const moe_layer* layers, int32_t n_la
         const int64_t p0 = it * step;
         const int64_t pn = (P == 0) ? 0 : ((p0 + step <= P) ? step : P - p0);
         const int64_t T = D + pn;
-        // hybrid batch: decode rows first, then this iteration's prefill rows
+        // hybrid batch: decode rows first, then this iteration's prefill rows; the first layer reads the two
+        // pieces where they are, later layers read the context's ping-pong buffers
         char* cur = static_cast<char*>(ctx->xa);
         char* nxt = static_cast<char*>(ctx->xb);
-        if (D > 0 && hipMemcpyAsync(cur, x_decode, D * row_bytes, hipMemcpyDeviceToDevice, s) != hipSuccess)
-            return MOE_ERR_DEVICE;
-        if (pn > 0 && hipMemcpyAsync(cur + D * row_bytes, static_cast<const char*>(x_prefill) + p0 * row_bytes,
-                                     pn * row_bytes, hipMemcpyDeviceToDevice, s) != hipSuccess)
-            return MOE_ERR_DEVICE;
+        const RowSrc first{x_decode, D, static_cast<const char*>(x_prefill) + p0 * row_bytes};
         for (int l = 0; l < n_layers; ++l) {
+            const RowSrc in = (l == 0) ? first : single_src(cur);
             moe_status st;
             if (l + 1 < n_layers) {
-                st = run_layer(ctx, layers[l], cur, T, nxt, T, nxt, s);
+                st = run_layer(ctx, layers[l], in, T, nxt, T, nxt, s);
             } else {
                 void* yp = (P > 0) ? static_cast<char*>(y_prefill) + p0 * row_bytes : nullptr;
-                st = run_layer(ctx, layers[l], cur, T, y_decode, D, yp, s);
+                st = run_layer(ctx, layers[l], in, T, y_decode, D, yp, s);
             }
             if (st != MOE_OK) return st;
             char* t = cur; cur = nxt; nxt = t;

@@ -38,8 +38,8 @@ template <> struct pack16<float> {
 // write decode rows and prefill rows to their separate output buffers without a copy.
 template <typename T>
 __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ y_perm, const int32_t* __restrict__ inv,
-                                                      const float* __restrict__ w, const T* residual, int K, int H,
-                                                      T* y0, int64_t rows0, T* y1)
+                                                      const float* __restrict__ w, bool has_residual,
+                                                      RowSrc residual, int K, int H, T* y0, int64_t rows0, T* y1)
 {
     typedef pack16<T> P;
     __shared__ int32_t s_row[kMaxTopK];
@@ -63,9 +63,9 @@ __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ y_pe
 #pragma unroll
             for (int i = 0; i < P::N; ++i) acc[i] = fmaf(wj, v[i], acc[i]);
         }
-        if (residual) {
+        if (has_residual) {
             P p;
-            p.raw = *reinterpret_cast<const decltype(p.raw)*>(residual + t * (int64_t)H + c);
+            p.raw = *reinterpret_cast<const decltype(p.raw)*>(row_ptr<T>(residual, t, H) + c);
             p.unpack(v);
 #pragma unroll
             for (int i = 0; i < P::N; ++i) acc[i] += v[i];
@@ -76,14 +76,14 @@ __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ y_pe
     }
 }
 
-hipError_t launch_combine(int dtype, const void* y_perm, const int32_t* inv, const float* w, const void* residual,
-                          int64_t T, int K, int H, void* y0, int64_t rows0, void* y1, hipStream_t s)
+hipError_t launch_combine(int dtype, const void* y_perm, const int32_t* inv, const float* w, bool has_residual,
+                          RowSrc residual, int64_t T, int K, int H, void* y0, int64_t rows0, void* y1, hipStream_t s)
 {
     if (dtype == MOE_BF16)
-        combine_kernel<bf16_t><<<(unsigned)T, 256, 0, s>>>((const bf16_t*)y_perm, inv, w, (const bf16_t*)residual, K,
+        combine_kernel<bf16_t><<<(unsigned)T, 256, 0, s>>>((const bf16_t*)y_perm, inv, w, has_residual, residual, K,
                                                            H, (bf16_t*)y0, rows0, (bf16_t*)y1);
     else
-        combine_kernel<float><<<(unsigned)T, 256, 0, s>>>((const float*)y_perm, inv, w, (const float*)residual, K, H,
+        combine_kernel<float><<<(unsigned)T, 256, 0, s>>>((const float*)y_perm, inv, w, has_residual, residual, K, H,
                                                           (float*)y0, rows0, (float*)y1);
     return hipGetLastError();
 }

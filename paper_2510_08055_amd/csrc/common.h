@@ -41,29 +41,46 @@ template <> struct elem<bf16_t> {
 
 __device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & 63); }
 
+// A batch of rows that lives in two buffers: rows [0, n0) in p0, the rest in p1 (row t - n0).  The
+// layer-group driver reads the first layer's input straight from x_decode / x_prefill this way instead
+// of copying the two pieces together first.
+struct RowSrc {
+    const void* p0;
+    int64_t n0;
+    const void* p1;
+};
+inline RowSrc single_src(const void* p) { return RowSrc{p, (int64_t)1 << 62, p}; }
+template <typename T> __device__ __forceinline__ const T* row_ptr(const RowSrc& s, int64_t t, int64_t ld)
+{
+    return t < s.n0 ? static_cast<const T*>(s.p0) + t * ld : static_cast<const T*>(s.p1) + (t - s.n0) * ld;
+}
+
 // ---- launchers implemented in the .hip files; all return hipError_t from hipGetLastError() ----
 
 // router.hip
-hipError_t launch_router_logits(int dtype, const void* x, int64_t T, int H, const void* w_router,
-                                const float* bias, int E, double* logits, hipStream_t s);
+hipError_t launch_router_logits(int dtype, RowSrc x, int64_t T, int H, const void* w_router, const float* bias,
+                                int E, double* logits, int32_t* zero_buf, int zero_n, hipStream_t s);
+// tile_hist (or NULL): [ceil(T*K / kPermTile), E] counters, already zero, that receive the expert histogram
 hipError_t launch_topk(const double* logits, int64_t T, int E, int K, int renorm, int32_t* idx, float* w,
-                       hipStream_t s);
+                       int32_t* tile_hist, hipStream_t s);
 
 // permute.hip
 constexpr int kPermTile = 8192;  // assignments per block of the permutation kernels
+// hist_ready: tile_hist already holds the per-tile histograms (the top-k kernel counted them)
 hipError_t launch_permute(const int32_t* idx, int64_t A, int E, int32_t* counts, int32_t* offsets,
-                          int32_t* perm, int32_t* inv, int32_t* tile_hist, unsigned long long* active_total,
-                          hipStream_t s);
+                          int32_t* perm, int32_t* inv, int32_t* tile_hist, bool hist_ready,
+                          unsigned long long* active_total, hipStream_t s);
 hipError_t launch_gather_rows(int dtype, const void* x, const int32_t* perm, int K, int64_t A, int H,
                               void* x_perm, hipStream_t s);
 
 // combine.hip
-hipError_t launch_combine(int dtype, const void* y_perm, const int32_t* inv, const float* w, const void* residual,
-                          int64_t T, int K, int H, void* y0, int64_t rows0, void* y1, hipStream_t s);
+hipError_t launch_combine(int dtype, const void* y_perm, const int32_t* inv, const float* w, bool has_residual,
+                          RowSrc residual, int64_t T, int K, int H, void* y0, int64_t rows0, void* y1,
+                          hipStream_t s);
 
 // ffn.hip
 // x: [*, H]; row_map (or NULL): permuted row r reads x row row_map[r] / map_div; offsets [E+1].
-hipError_t launch_ffn_gate_up(int dtype, const void* x, const int32_t* row_map, int map_div,
+hipError_t launch_ffn_gate_up(int dtype, RowSrc x, const int32_t* row_map, int map_div,
                               const int32_t* offsets, int64_t A, int E, int H, int I, const void* w_gate_up,
                               void* act, hipStream_t s);
 hipError_t launch_ffn_down(int dtype, const void* act, const int32_t* offsets, int64_t A, int E, int H, int I,

@@ -116,7 +116,7 @@ __device__ __forceinline__ float silu_mul(float g, float u) { return g / (1.0f +
 // ----------------------------------------------------------------------------------------------
 template <int BM, int BN, bool GATED>
 __global__ __launch_bounds__(256) void grouped_gemm_bf16_kernel(
-    const bf16_t* __restrict__ X, int ldx, const int32_t* __restrict__ row_map, int map_div,
+    RowSrc X, int ldx, const int32_t* __restrict__ row_map, int map_div,
     const int32_t* __restrict__ offsets, int E, const bf16_t* __restrict__ W, int64_t w_expert_stride, int N, int K,
     bf16_t* __restrict__ Out, int ldo)
 {
@@ -150,7 +150,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16_kernel(
         int r = tc.row0 + ld_row + 32 * p;
         if (r >= tc.row_end) r = tc.row_end - 1;            // ragged tail: re-read a valid row, result unused
         const int64_t src = row_map ? (int64_t)(row_map[r] / map_div) : (int64_t)r;
-        a_src[p] = X + src * ldx + ld_chunk * 8;
+        a_src[p] = row_ptr<bf16_t>(X, src, ldx) + ld_chunk * 8;
     }
 #pragma unroll
     for (int p = 0; p < B_LOADS; ++p) {
@@ -287,7 +287,7 @@ template <int PBK> __device__ __forceinline__ int swz(int r)
 
 template <int RBM, int BN, int WM, int NSTAGE, int PBK, int MINW, bool GATED>
 __global__ __launch_bounds__(256, MINW) void grouped_gemm_bf16_pipe_kernel(
-    const bf16_t* __restrict__ X, int ldx, const int32_t* __restrict__ row_map, int map_div,
+    RowSrc X, int ldx, const int32_t* __restrict__ row_map, int map_div,
     const int32_t* __restrict__ offsets, int E, const bf16_t* __restrict__ W, int64_t w_expert_stride, int N, int K,
     bf16_t* __restrict__ Out, int ldo)
 {
@@ -333,7 +333,7 @@ __global__ __launch_bounds__(256, MINW) void grouped_gemm_bf16_pipe_kernel(
         int r = tc.row0 + tr;
         if (r >= tc.row_end) r = tc.row_end - 1;
         const int64_t src = row_map ? (int64_t)(row_map[r] / map_div) : (int64_t)r;
-        a_src[p] = X + src * ldx + ((l_chunk ^ swz<PBK>(tr)) << 3);
+        a_src[p] = row_ptr<bf16_t>(X, src, ldx) + ((l_chunk ^ swz<PBK>(tr)) << 3);
     }
 #pragma unroll
     for (int p = 0; p < B_LPW; ++p) {
@@ -523,7 +523,7 @@ __device__ __forceinline__ int expert_of_row(const int32_t* __restrict__ offsets
 }
 
 template <bool GATED>
-__global__ __launch_bounds__(256) void grouped_gemm_f32_kernel(const float* __restrict__ X, int ldx,
+__global__ __launch_bounds__(256) void grouped_gemm_f32_kernel(RowSrc X, int ldx,
                                                                const int32_t* __restrict__ row_map, int map_div,
                                                                const int32_t* __restrict__ offsets, int E,
                                                                const float* __restrict__ W, int64_t w_expert_stride,
@@ -535,7 +535,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_f32_kernel(const float* __re
     const int r = (int)(g / N), n = (int)(g % N);
     const int e = expert_of_row(offsets, E, r);
     const int64_t src = row_map ? (int64_t)(row_map[r] / map_div) : (int64_t)r;
-    const float* x = X + src * ldx;
+    const float* x = row_ptr<float>(X, src, ldx);
     const float* w0 = W + (int64_t)e * w_expert_stride + (int64_t)n * K;
     float s0 = 0.f, s1 = 0.f;
     for (int k = 0; k < K; ++k) s0 = fmaf(x[k], w0[k], s0);
@@ -572,7 +572,7 @@ static Variant pick_variant(int64_t A, int E, int K)
 }
 
 template <int BM, int BN, bool GATED>
-static hipError_t launch_tile(const bf16_t* X, int ldx, const int32_t* row_map, int map_div, const int32_t* offsets,
+static hipError_t launch_tile(RowSrc X, int ldx, const int32_t* row_map, int map_div, const int32_t* offsets,
                               int E, int64_t A, const bf16_t* W, int64_t w_expert_stride, int N, int K, bf16_t* Out,
                               int ldo, hipStream_t s)
 {
@@ -595,7 +595,7 @@ static hipError_t launch_tile(const bf16_t* X, int ldx, const int32_t* row_map, 
 }
 
 template <int RBM, int BN, int WM, int NSTAGE, int PBK, int MINW, bool GATED>
-static hipError_t launch_pipe(const bf16_t* X, int ldx, const int32_t* row_map, int map_div, const int32_t* offsets,
+static hipError_t launch_pipe(RowSrc X, int ldx, const int32_t* row_map, int map_div, const int32_t* offsets,
                               int E, int64_t A, const bf16_t* W, int64_t w_expert_stride, int N, int K, bf16_t* Out,
                               int ldo, hipStream_t s)
 {
@@ -619,7 +619,7 @@ static hipError_t launch_pipe(const bf16_t* X, int ldx, const int32_t* row_map, 
 }
 
 template <bool GATED>
-static hipError_t launch_bf16(const bf16_t* X, int ldx, const int32_t* row_map, int map_div, const int32_t* offsets,
+static hipError_t launch_bf16(RowSrc X, int ldx, const int32_t* row_map, int map_div, const int32_t* offsets,
                               int E, int64_t A, const bf16_t* W, int64_t w_expert_stride, int N, int K, bf16_t* Out,
                               int ldo, hipStream_t s)
 {
@@ -634,14 +634,14 @@ static hipError_t launch_bf16(const bf16_t* X, int ldx, const int32_t* row_map, 
     }
 }
 
-hipError_t launch_ffn_gate_up(int dtype, const void* x, const int32_t* row_map, int map_div, const int32_t* offsets,
+hipError_t launch_ffn_gate_up(int dtype, RowSrc x, const int32_t* row_map, int map_div, const int32_t* offsets,
                               int64_t A, int E, int H, int I, const void* w_gate_up, void* act, hipStream_t s)
 {
     if (dtype == MOE_BF16)
-        return launch_bf16<true>((const bf16_t*)x, H, row_map, map_div, offsets, E, A, (const bf16_t*)w_gate_up,
+        return launch_bf16<true>(x, H, row_map, map_div, offsets, E, A, (const bf16_t*)w_gate_up,
                                  (int64_t)2 * I * H, I, H, (bf16_t*)act, I, s);
     const unsigned grid = (unsigned)((A * I + 255) / 256);
-    grouped_gemm_f32_kernel<true><<<grid, 256, 0, s>>>((const float*)x, H, row_map, map_div, offsets, E,
+    grouped_gemm_f32_kernel<true><<<grid, 256, 0, s>>>(x, H, row_map, map_div, offsets, E,
                                                        (const float*)w_gate_up, (int64_t)2 * I * H, I, H, A,
                                                        (float*)act, I);
     return hipGetLastError();
@@ -651,10 +651,10 @@ hipError_t launch_ffn_down(int dtype, const void* act, const int32_t* offsets, i
                            const void* w_down, void* y_perm, hipStream_t s)
 {
     if (dtype == MOE_BF16)
-        return launch_bf16<false>((const bf16_t*)act, I, nullptr, 1, offsets, E, A, (const bf16_t*)w_down,
+        return launch_bf16<false>(single_src(act), I, nullptr, 1, offsets, E, A, (const bf16_t*)w_down,
                                   (int64_t)H * I, H, I, (bf16_t*)y_perm, H, s);
     const unsigned grid = (unsigned)((A * H + 255) / 256);
-    grouped_gemm_f32_kernel<false><<<grid, 256, 0, s>>>((const float*)act, I, nullptr, 1, offsets, E,
+    grouped_gemm_f32_kernel<false><<<grid, 256, 0, s>>>(single_src(act), I, nullptr, 1, offsets, E,
                                                         (const float*)w_down, (int64_t)H * I, H, I, A,
                                                         (float*)y_perm, H);
     return hipGetLastError();

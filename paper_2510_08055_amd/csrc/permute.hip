@@ -170,10 +170,11 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const VT* __restrict__
 }
 
 hipError_t launch_permute(const int32_t* idx, int64_t A, int E, int32_t* counts, int32_t* offsets, int32_t* perm,
-                          int32_t* inv, int32_t* tile_hist, unsigned long long* active_total, hipStream_t s)
+                          int32_t* inv, int32_t* tile_hist, bool hist_ready, unsigned long long* active_total,
+                          hipStream_t s)
 {
     const int n_tiles = (int)((A + kPermTile - 1) / kPermTile);
-    if (n_tiles > 1) {
+    if (n_tiles > 1 && !hist_ready) {
         permute_hist_kernel<<<n_tiles, kPermThreads, 0, s>>>(idx, A, E, tile_hist);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;

@@ -46,12 +46,17 @@ template <> struct vec8<float> {
 // k-values [c*32 + q*8, c*32 + q*8 + 8) of chunk c and feeds them to 8 successive MFMAs (any fixed
 // pairing of k-slots is a valid summation order).  Many short waves per SIMD hide the load latency.
 template <typename T>
-__global__ __launch_bounds__(256) void router_logits_kernel(const T* __restrict__ x, int64_t n_tok, int H,
+__global__ __launch_bounds__(256) void router_logits_kernel(RowSrc x, int64_t n_tok, int H,
                                                             const T* __restrict__ wr,
                                                             const float* __restrict__ bias, int E,
-                                                            double* __restrict__ logits)
+                                                            double* __restrict__ logits,
+                                                            int32_t* __restrict__ zero_buf, int zero_n)
 {
     __shared__ double part[3][4][64];   // partial tiles of waves 1..3: [wave-1][element v][lane]
+    // side job of block (0,0): clear the per-tile expert histogram that the top-k kernel, next on the
+    // stream, counts into (saves a separate fill launch)
+    if (blockIdx.x == 0 && blockIdx.y == 0)
+        for (int i = threadIdx.x; i < zero_n; i += 256) zero_buf[i] = 0;
     const int lane = lane_id();
     const int wave = threadIdx.x >> 6;
     const int r = lane & 15, q = lane >> 4;
@@ -59,7 +64,7 @@ __global__ __launch_bounds__(256) void router_logits_kernel(const T* __restrict_
     const int e0 = blockIdx.y * 16;
     const int64_t tr = (t0 + r < n_tok) ? (t0 + r) : (n_tok - 1);  // clamp: loads stay in bounds
     const int er = (e0 + r < E) ? (e0 + r) : (E - 1);
-    const T* xp = x + tr * (int64_t)H + q * 8;
+    const T* xp = row_ptr<T>(x, tr, H) + q * 8;
     const T* wp = wr + (int64_t)er * H + q * 8;
 
     double4_t acc = {0.0, 0.0, 0.0, 0.0};
@@ -104,7 +109,8 @@ __device__ __forceinline__ bool before(double va, int ia, double vb, int ib)
 // arg-max, each removing the winner.  Lane j keeps the j-th winner and computes its weight.
 template <int NPL>
 __global__ __launch_bounds__(256) void topk_kernel(const double* __restrict__ logits, int64_t n_tok, int E, int K,
-                                                   int renorm, int32_t* __restrict__ idx, float* __restrict__ w)
+                                                   int renorm, int32_t* __restrict__ idx, float* __restrict__ w,
+                                                   int32_t* __restrict__ tile_hist)
 {
     const int lane = lane_id();
     const int64_t t = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -159,31 +165,33 @@ __global__ __launch_bounds__(256) void topk_kernel(const double* __restrict__ lo
     if (lane < K) {
         idx[t * K + lane] = my_e;
         w[t * K + lane] = (float)(p / denom);
+        // per-tile expert histogram for the permutation (integer atomics: the counts do not depend on order)
+        if (tile_hist) atomicAdd(&tile_hist[((t * K + lane) / kPermTile) * E + my_e], 1);
     }
 }
 
-hipError_t launch_router_logits(int dtype, const void* x, int64_t T, int H, const void* w_router,
-                                const float* bias, int E, double* logits, hipStream_t s)
+hipError_t launch_router_logits(int dtype, RowSrc x, int64_t T, int H, const void* w_router, const float* bias,
+                                int E, double* logits, int32_t* zero_buf, int zero_n, hipStream_t s)
 {
     dim3 grid((unsigned)((T + 15) / 16), (unsigned)((E + 15) / 16));
     if (dtype == MOE_BF16)
-        router_logits_kernel<bf16_t><<<grid, 256, 0, s>>>((const bf16_t*)x, T, H, (const bf16_t*)w_router, bias, E,
-                                                          logits);
+        router_logits_kernel<bf16_t><<<grid, 256, 0, s>>>(x, T, H, (const bf16_t*)w_router, bias, E, logits, zero_buf,
+                                                          zero_n);
     else
-        router_logits_kernel<float><<<grid, 256, 0, s>>>((const float*)x, T, H, (const float*)w_router, bias, E,
-                                                         logits);
+        router_logits_kernel<float><<<grid, 256, 0, s>>>(x, T, H, (const float*)w_router, bias, E, logits, zero_buf,
+                                                         zero_n);
     return hipGetLastError();
 }
 
 hipError_t launch_topk(const double* logits, int64_t T, int E, int K, int renorm, int32_t* idx, float* w,
-                       hipStream_t s)
+                       int32_t* tile_hist, hipStream_t s)
 {
     const unsigned grid = (unsigned)((T + 3) / 4);
     const int npl = (E + 63) / 64;
-    if (npl <= 1) topk_kernel<1><<<grid, 256, 0, s>>>(logits, T, E, K, renorm, idx, w);
-    else if (npl <= 2) topk_kernel<2><<<grid, 256, 0, s>>>(logits, T, E, K, renorm, idx, w);
-    else if (npl <= 4) topk_kernel<4><<<grid, 256, 0, s>>>(logits, T, E, K, renorm, idx, w);
-    else topk_kernel<8><<<grid, 256, 0, s>>>(logits, T, E, K, renorm, idx, w);
+    if (npl <= 1) topk_kernel<1><<<grid, 256, 0, s>>>(logits, T, E, K, renorm, idx, w, tile_hist);
+    else if (npl <= 2) topk_kernel<2><<<grid, 256, 0, s>>>(logits, T, E, K, renorm, idx, w, tile_hist);
+    else if (npl <= 4) topk_kernel<4><<<grid, 256, 0, s>>>(logits, T, E, K, renorm, idx, w, tile_hist);
+    else topk_kernel<8><<<grid, 256, 0, s>>>(logits, T, E, K, renorm, idx, w, tile_hist);
     return hipGetLastError();
 }
 
