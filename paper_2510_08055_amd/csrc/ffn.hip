@@ -414,7 +414,9 @@ __global__ __launch_bounds__(256, MINW) void grouped_gemm_bf16_pipe_kernel(
             for (int i = 0; i < TMV; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[set][i], bfr[set][j], acc[i][j], 0, 0, 0);
+                    // weight rows as the MFMA's row operand, activation rows as its column operand: a lane then
+                    // holds 4 consecutive OUTPUT COLUMNS of one output row, which the epilogue stores as 8 bytes
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[set][j], af[set][i], acc[i][j], 0, 0, 0);
         };
 
 #pragma unroll
@@ -485,16 +487,22 @@ __global__ __launch_bounds__(256, MINW) void grouped_gemm_bf16_pipe_kernel(
 
 #pragma unroll
         for (int i = 0; i < TMV; ++i) {
+            // accumulator element v of tile (i, j): output row fr of row block i, column (v/4)*8 + fq*4 + v%4
+            const int row = tc.row0 + (wm + WM * i) * 32 + fr;
 #pragma unroll
             for (int j = 0; j < TNO; ++j) {
-                const int col = n0 + wn * WNO + j * 32 + fr;
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int row = tc.row0 + (wm + WM * i) * 32 + (v >> 2) * 8 + fq * 4 + (v & 3);
-                    float val;
-                    if (GATED) val = silu_mul(acc[i][j][v], acc[i][j + TNO][v]);
-                    else val = acc[i][j][v];
-                    if (row < tc.row_end && col < N) Out[(int64_t)row * ldo + col] = f32_to_bf16(val);
+                for (int a = 0; a < 4; ++a) {
+                    const int col = n0 + wn * WNO + j * 32 + a * 8 + fq * 4;
+                    float val[4];
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+                        if (GATED) val[b] = silu_mul(acc[i][j][a * 4 + b], acc[i][j + TNO][a * 4 + b]);
+                        else val[b] = acc[i][j][a * 4 + b];
+                    }
+                    if (row < tc.row_end && col < N)    // N is a multiple of 8: the 4 columns are in or out together
+                        *reinterpret_cast<uint2*>(Out + (int64_t)row * ldo + col) =
+                            make_uint2(pack_bf16x2(val[0], val[1]), pack_bf16x2(val[2], val[3]));
                 }
             }
         }
