@@ -250,10 +250,10 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16_kernel(
 // Pipelined grouped GEMM: global -> LDS copies issued as direct-to-LDS loads
 // (global_load_lds_dwordx4: no staging registers, no LDS store instructions), NSTAGE stages of
 // PBK (64 or 32) k-values in flight, one barrier per stage.  Used for both regimes of Sec. 2.5:
-//   - weight streaming (few rows per expert): WM = 1, the 4 waves split the weight rows, each wave
-//     multiplies all RBM row blocks; deep staging keeps >= 64 KB of loads in flight per CU.
-//   - compute bound (hundreds of rows per expert): WM = 2, 2x2 waves with large wave tiles so that
-//     LDS operand traffic per MFMA stays low.
+//   - weight streaming (few rows per expert): 64-row tiles, 3 stages of 64 k-values (40 KB each);
+//   - compute bound (hundreds of rows per expert): up to 256-row tiles, 4 stages of 32 k-values.
+// NW waves arranged WM x WN; with 8 waves (2 per SIMD) one wave's barrier and LDS waits are covered
+// by the other's MFMAs.
 // One wave-level load moves 64 lanes x 16 B = 8 (or 16) whole tile rows into 1 KB of LDS.  LDS rows
 // are unpadded (the hardware writes lanes contiguously), so bank conflicts on the 16-byte operand
 // reads are avoided by an XOR swizzle applied on the SOURCE side: LDS chunk c of tile row r holds
@@ -285,13 +285,13 @@ template <int PBK> __device__ __forceinline__ int swz(int r)
     return ((r >> 1) & 3) ^ ((r >> 3) & 1);
 }
 
-template <int RBM, int BN, int WM, int NSTAGE, int PBK, int MINW, bool GATED>
-__global__ __launch_bounds__(256, MINW) void grouped_gemm_bf16_pipe_kernel(
+template <int RBM, int BN, int WM, int NSTAGE, int PBK, int MINW, int NW, bool GATED>
+__global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
     RowSrc X, int ldx, const int32_t* __restrict__ row_map, int map_div,
     const int32_t* __restrict__ offsets, int E, const bf16_t* __restrict__ W, int64_t w_expert_stride, int N, int K,
     bf16_t* __restrict__ Out, int ldo)
 {
-    constexpr int BM = RBM * 32, WN = 4 / WM;
+    constexpr int BM = RBM * 32, WN = NW / WM;   // NW waves arranged WM (rows) x WN (columns)
     constexpr int NO = GATED ? BN / 2 : BN;     // output columns per block
     constexpr int TM = RBM / WM;                // row blocks per wave: rb = wm + WM * i
     constexpr int WNO = NO / WN;                // output columns per wave
@@ -301,12 +301,12 @@ __global__ __launch_bounds__(256, MINW) void grouped_gemm_bf16_pipe_kernel(
     constexpr int CPR = PBK / 8;                        // 16-byte chunks per row
     constexpr int RPL = 64 / CPR;                       // tile rows moved by one wave-level load (1 KB)
     constexpr int KS = PBK / 16;                        // MFMA k-slices per stage
-    constexpr int A_LPW = BM / RPL / 4, B_LPW = BN / RPL / 4;   // load groups per wave and stage
+    constexpr int A_LPW = BM / RPL / NW, B_LPW = BN / RPL / NW;   // load groups per wave and stage
     constexpr int LPS = A_LPW + B_LPW;                  // load instructions per thread and stage
     constexpr int STAGE = (BM + BN) * ROWB;             // bytes
     static_assert(PBK == 64 || PBK == 32, "stage depth must be 64 or 32");
     static_assert(RBM % WM == 0 && TM <= 4 && TNO >= 1 && (NSTAGE - 2) * LPS < 64, "bad tile configuration");
-    static_assert(BM % (RPL * 4) == 0 && BN % (RPL * 4) == 0, "tile rows must split evenly over the four waves");
+    static_assert(BM % (RPL * NW) == 0 && BN % (RPL * NW) == 0, "tile rows must split evenly over the waves");
     constexpr int WAIT_MAIN = (NSTAGE - 2) * LPS;   // loads younger than the stage waited for
     static_assert(WAIT_MAIN < 64, "vmcnt is a 6-bit counter");
 
@@ -323,13 +323,13 @@ __global__ __launch_bounds__(256, MINW) void grouped_gemm_bf16_pipe_kernel(
     const int rows_here = (tc.row_end - tc.row0) < BM ? (tc.row_end - tc.row0) : BM;
     const int rb_valid = (rows_here + 31) / 32;   // row blocks of this tile with at least one real row
 
-    // ---- source addresses of this lane's loads: group g = wave + 4*p covers tile rows RPL*g .. RPL*g + RPL-1 ----
+    // ---- source addresses of this lane's loads: group g = wave + NW*p covers tile rows RPL*g .. RPL*g + RPL-1 ----
     const int l_row = lane / CPR, l_chunk = lane % CPR;
     const bf16_t* a_src[A_LPW];
     const bf16_t* b_src[B_LPW];
 #pragma unroll
     for (int p = 0; p < A_LPW; ++p) {
-        const int tr = (wave + 4 * p) * RPL + l_row;      // row inside the tile
+        const int tr = (wave + NW * p) * RPL + l_row;      // row inside the tile
         int r = tc.row0 + tr;
         if (r >= tc.row_end) r = tc.row_end - 1;
         const int64_t src = row_map ? (int64_t)(row_map[r] / map_div) : (int64_t)r;
@@ -337,7 +337,7 @@ __global__ __launch_bounds__(256, MINW) void grouped_gemm_bf16_pipe_kernel(
     }
 #pragma unroll
     for (int p = 0; p < B_LPW; ++p) {
-        const int rb = (wave + 4 * p) * RPL + l_row;
+        const int rb = (wave + NW * p) * RPL + l_row;
         int n;
         if (GATED) n = (rb < NO) ? (n0 + rb) : (n0 + rb - NO);
         else n = n0 + rb;
@@ -355,10 +355,10 @@ __global__ __launch_bounds__(256, MINW) void grouped_gemm_bf16_pipe_kernel(
             if (p % KS != part) continue;
             if (p < A_LPW)
                 __builtin_amdgcn_global_load_lds((glb_ptr_t*)(a_src[p] + k0),
-                                                 (lds_ptr_t*)(base + (wave + 4 * p) * 1024), 16, 0, 0);
+                                                 (lds_ptr_t*)(base + (wave + NW * p) * 1024), 16, 0, 0);
             else
                 __builtin_amdgcn_global_load_lds((glb_ptr_t*)(b_src[p - A_LPW] + k0),
-                                                 (lds_ptr_t*)(base + BM * ROWB + (wave + 4 * (p - A_LPW)) * 1024), 16,
+                                                 (lds_ptr_t*)(base + BM * ROWB + (wave + NW * (p - A_LPW)) * 1024), 16,
                                                  0, 0);
         }
     };
@@ -561,19 +561,19 @@ __global__ __launch_bounds__(256) void grouped_gemm_f32_kernel(RowSrc X, int ldx
 // the device), so the variant is chosen from the mean rows per expert A/E; every variant is correct
 // for any distribution of rows.
 // ----------------------------------------------------------------------------------------------
-enum Variant { V_TILE128 = 0, V_PIPE_S2, V_PIPE_B8 };
+enum Variant { V_TILE128 = 0, V_PIPE_SMALL, V_PIPE_BIG };
 
 static Variant pick_variant(int64_t A, int E, int K)
 {
-    static const char* force = getenv("MOE_FFN_VARIANT");   // tuning aid: "tile128", "pipe_s2", "pipe_b8"
+    static const char* force = getenv("MOE_FFN_VARIANT");   // tuning aid: "tile128", "small", "big"
     Variant v;
     const double mean_rows = (double)A / (double)E;
-    if (mean_rows <= 64.0) v = V_PIPE_S2;      // weight streaming: 64-row tiles, 4 waves across the weight rows
-    else v = V_PIPE_B8;                        // up to 256-row tiles, 2x2 waves of 128x128
+    if (mean_rows <= 64.0) v = V_PIPE_SMALL;   // weight streaming: 64-row tiles, 3 stages of 64 k-values
+    else v = V_PIPE_BIG;                       // up to 256-row tiles, 4 stages of 32 k-values
     if (force) {
         if (!strcmp(force, "tile128")) v = V_TILE128;
-        if (!strcmp(force, "pipe_s2")) v = V_PIPE_S2;
-        if (!strcmp(force, "pipe_b8")) v = V_PIPE_B8;
+        if (!strcmp(force, "small")) v = V_PIPE_SMALL;
+        if (!strcmp(force, "big")) v = V_PIPE_BIG;
     }
     if (K % 64 != 0) v = V_TILE128;            // the pipelined kernels have no k-tail path
     return v;
@@ -602,7 +602,7 @@ static hipError_t launch_tile(RowSrc X, int ldx, const int32_t* row_map, int map
     return hipGetLastError();
 }
 
-template <int RBM, int BN, int WM, int NSTAGE, int PBK, int MINW, bool GATED>
+template <int RBM, int BN, int WM, int NSTAGE, int PBK, int MINW, int NW, bool GATED>
 static hipError_t launch_pipe(RowSrc X, int ldx, const int32_t* row_map, int map_div, const int32_t* offsets,
                               int E, int64_t A, const bf16_t* W, int64_t w_expert_stride, int N, int K, bf16_t* Out,
                               int ldo, hipStream_t s)
@@ -610,7 +610,7 @@ static hipError_t launch_pipe(RowSrc X, int ldx, const int32_t* row_map, int map
     constexpr int BM = RBM * 32;
     constexpr int NO = GATED ? BN / 2 : BN;
     const size_t lds_bytes = (size_t)NSTAGE * (BM + BN) * PBK * 2;
-    auto kern = grouped_gemm_bf16_pipe_kernel<RBM, BN, WM, NSTAGE, PBK, MINW, GATED>;
+    auto kern = grouped_gemm_bf16_pipe_kernel<RBM, BN, WM, NSTAGE, PBK, MINW, NW, GATED>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -621,7 +621,7 @@ static hipError_t launch_pipe(RowSrc X, int ldx, const int32_t* row_map, int map
     const int64_t n_tiles = (N + NO - 1) / NO;
     const int64_t m_tiles_max = (A + BM - 1) / BM + (A < E ? A : E);
     const int64_t grid = ((m_tiles_max * n_tiles + 7) / 8) * 8;
-    kern<<<(unsigned)grid, 256, lds_bytes, s>>>(X, ldx, row_map, map_div, offsets, E, W, w_expert_stride, N, K, Out,
+    kern<<<(unsigned)grid, NW * 64, lds_bytes, s>>>(X, ldx, row_map, map_div, offsets, E, W, w_expert_stride, N, K, Out,
                                                 ldo);
     return hipGetLastError();
 }
@@ -631,11 +631,13 @@ static hipError_t launch_bf16(RowSrc X, int ldx, const int32_t* row_map, int map
                               int E, int64_t A, const bf16_t* W, int64_t w_expert_stride, int N, int K, bf16_t* Out,
                               int ldo, hipStream_t s)
 {
+    // both pipelined variants: 8 waves (2 per SIMD, so one wave's barrier / LDS waits are covered by the
+    // other's MFMAs), 2 (rows) x 4 (columns), 256 weight rows per block
     switch (pick_variant(A, E, K)) {
-        case V_PIPE_S2:
-            return launch_pipe<2, 256, 1, 3, 64, 1, GATED>(X, ldx, row_map, map_div, offsets, E, A, W, w_expert_stride, N, K, Out, ldo, s);
-        case V_PIPE_B8:
-            return launch_pipe<8, 256, 2, 4, 32, 1, GATED>(X, ldx, row_map, map_div, offsets, E, A, W, w_expert_stride, N, K, Out, ldo, s);
+        case V_PIPE_SMALL:
+            return launch_pipe<2, 256, 2, 3, 64, 2, 8, GATED>(X, ldx, row_map, map_div, offsets, E, A, W, w_expert_stride, N, K, Out, ldo, s);
+        case V_PIPE_BIG:
+            return launch_pipe<8, 256, 2, 4, 32, 2, 8, GATED>(X, ldx, row_map, map_div, offsets, E, A, W, w_expert_stride, N, K, Out, ldo, s);
         default:
             return launch_tile<128, 128, GATED>(X, ldx, row_map, map_div, offsets, E, A, W, w_expert_stride, N, K, Out,
                                                 ldo, s);
@@ -673,8 +675,8 @@ const char* ffn_variant_name(int dtype, int64_t A, int E, int H, int I)
     (void)I;
     if (dtype != MOE_BF16) return "grouped_gemm_f32_kernel<gated>";
     switch (pick_variant(A, E, H)) {
-        case V_PIPE_S2: return "grouped_gemm_bf16_pipe_kernel<2,256,1,3,64,gated>";
-        case V_PIPE_B8: return "grouped_gemm_bf16_pipe_kernel<8,256,2,4,32,gated>";
+        case V_PIPE_SMALL: return "grouped_gemm_bf16_pipe_kernel<2,256,2,3,64,2,8,gated>";
+        case V_PIPE_BIG: return "grouped_gemm_bf16_pipe_kernel<8,256,2,4,32,2,8,gated>";
         default: return "grouped_gemm_bf16_kernel<128,128,gated>";
     }
 }
