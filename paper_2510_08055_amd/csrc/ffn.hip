@@ -248,10 +248,14 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16_kernel(
 
 // ----------------------------------------------------------------------------------------------
 // Pipelined grouped GEMM: global -> LDS copies issued as direct-to-LDS loads
-// (global_load_lds_dwordx4: no staging registers, no LDS store instructions), NSTAGE stages of
-// PBK (64 or 32) k-values in flight, one barrier per stage.  Used for both regimes of Sec. 2.5:
-//   - weight streaming (few rows per expert): 64-row tiles, 3 stages of 64 k-values (40 KB each);
-//   - compute bound (hundreds of rows per expert): up to 256-row tiles, 4 stages of 32 k-values.
+// (global_load_lds_dwordx4: no staging registers, no LDS store instructions) into two rings of LDS
+// slots, NSA stages of the activation rows and NSB stages of the weight rows, each stage PBK (64 or
+// 32) k-values deep; one barrier per stage.  Used for both regimes of Sec. 2.5:
+//   - weight streaming (few rows per expert): 64 x 128 tiles, 3 + 3 stages of 64 k-values (24 KB each);
+//   - compute bound (hundreds of rows per expert): up to 256-row tiles with 64 k-values per stage, so
+//     that every tile row asks for a whole 128-byte line per stage (fewer, larger requests measured
+//     faster than 64-byte ones); 2 activation + 3 weight stages fill the 160 KB of LDS, the deeper
+//     ring going to the operand that comes from HBM.
 // NW waves arranged WM x WN; with 8 waves (2 per SIMD) one wave's barrier and LDS waits are covered
 // by the other's MFMAs.
 // One wave-level load moves 64 lanes x 16 B = 8 (or 16) whole tile rows into 1 KB of LDS.  LDS rows
@@ -285,7 +289,7 @@ template <int PBK> __device__ __forceinline__ int swz(int r)
     return ((r >> 1) & 3) ^ ((r >> 3) & 1);
 }
 
-template <int RBM, int BN, int WM, int NSTAGE, int PBK, int MINW, int NW, bool GATED>
+template <int RBM, int BN, int WM, int NSA, int NSB, int PBK, int MINW, int NW, int ORD, bool GATED>
 __global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
     RowSrc X, int ldx, const int32_t* __restrict__ row_map, int map_div,
     const int32_t* __restrict__ offsets, int E, const bf16_t* __restrict__ W, int64_t w_expert_stride, int N, int K,
@@ -303,12 +307,20 @@ __global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
     constexpr int KS = PBK / 16;                        // MFMA k-slices per stage
     constexpr int A_LPW = BM / RPL / NW, B_LPW = BN / RPL / NW;   // load groups per wave and stage
     constexpr int LPS = A_LPW + B_LPW;                  // load instructions per thread and stage
-    constexpr int STAGE = (BM + BN) * ROWB;             // bytes
+    constexpr int A_SLOT = BM * ROWB, B_SLOT = BN * ROWB;   // bytes of one stage of either operand
+    constexpr int B_BASE = NSA * A_SLOT;                // the weight ring follows the activation ring
+    constexpr int NSMIN = NSA < NSB ? NSA : NSB, NSMAX = NSA < NSB ? NSB : NSA;
     static_assert(PBK == 64 || PBK == 32, "stage depth must be 64 or 32");
-    static_assert(RBM % WM == 0 && TM <= 4 && TNO >= 1 && (NSTAGE - 2) * LPS < 64, "bad tile configuration");
+    static_assert(RBM % WM == 0 && TM <= 4 && TNO >= 1 && NSA >= 2 && NSB >= 2, "bad tile configuration");
+    static_assert(ORD == 0 ? NSA == NSB : ORD == 1 ? (NSB >= NSA) : (NSA >= NSB), "the shallower ring loads first");
     static_assert(BM % (RPL * NW) == 0 && BN % (RPL * NW) == 0, "tile rows must split evenly over the waves");
-    constexpr int WAIT_MAIN = (NSTAGE - 2) * LPS;   // loads younger than the stage waited for
-    static_assert(WAIT_MAIN < 64, "vmcnt is a 6-bit counter");
+    // In a step the loads of activation stage g+NSA-1 are issued first, those of weight stage g+NSB-1
+    // after them; loads return in issue order, so when stage g+1 is needed the loads that may still be
+    // in flight are the ones issued after activation stage g+1.
+    constexpr int WAIT_MAIN = (NSMIN - 2) * LPS + (NSA < NSB ? B_LPW : NSB < NSA ? A_LPW : 0);
+    constexpr int WAIT_FIRST = (NSA - 2) * A_LPW + (NSB - 2) * B_LPW;   // prologue loads after stage 0's
+    static_assert(NSMAX - NSMIN <= 1, "one ring is at most one stage deeper than the other");
+    static_assert(WAIT_MAIN < 64 && WAIT_FIRST < 64, "vmcnt is a 6-bit counter");
 
     extern __shared__ __attribute__((aligned(1024))) char smem[];
 
@@ -345,26 +357,33 @@ __global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
         if (GATED && rb >= NO) n += N;
         b_src[p] = We + (int64_t)n * K + ((l_chunk ^ swz<PBK>(rb)) << 3);
     }
-    // Load `part` (of KS) of stage kt into LDS buffer buf: the loads of a stage are spread over the
-    // k-slices of the stage being multiplied, so that they issue in the shadow of the MFMAs.
-    auto issue_part = [&](int kt, int buf, int part) {
-        char* base = smem + buf * STAGE;
-        const int k0 = kt * PBK;
-#pragma unroll
-        for (int p = 0; p < LPS; ++p) {
-            if (p % KS != part) continue;
-            if (p < A_LPW)
-                __builtin_amdgcn_global_load_lds((glb_ptr_t*)(a_src[p] + k0),
-                                                 (lds_ptr_t*)(base + (wave + NW * p) * 1024), 16, 0, 0);
-            else
-                __builtin_amdgcn_global_load_lds((glb_ptr_t*)(b_src[p - A_LPW] + k0),
-                                                 (lds_ptr_t*)(base + BM * ROWB + (wave + NW * (p - A_LPW)) * 1024), 16,
-                                                 0, 0);
-        }
+    // Loads of one stage, cut into KS parts that are issued in the shadow of the MFMAs of the KS
+    // k-slices of the stage being multiplied: load p of the step (activation loads first) goes with
+    // slice p * KS / LPS.
+    auto issue_a = [&](int kt, int p) {
+        __builtin_amdgcn_global_load_lds((glb_ptr_t*)(a_src[p] + kt * PBK),
+                                         (lds_ptr_t*)(smem + (kt % NSA) * A_SLOT + (wave + NW * p) * 1024), 16, 0, 0);
     };
-    auto issue_stage = [&](int kt, int buf) {
+    auto issue_b = [&](int kt, int p) {
+        __builtin_amdgcn_global_load_lds((glb_ptr_t*)(b_src[p] + kt * PBK),
+                                         (lds_ptr_t*)(smem + B_BASE + (kt % NSB) * B_SLOT + (wave + NW * p) * 1024), 16,
+                                         0, 0);
+    };
+    // Load q of a step: ORD 0 alternates over the parts as A0 B0 | A1 B1 ..., ORD 1 issues the activation
+    // loads first, ORD 2 the weight loads first.
+    auto load_is_a = [](int q) { return ORD == 2 ? q >= B_LPW : q < A_LPW; };
+    auto load_idx = [](int q) { return ORD == 2 ? (q >= B_LPW ? q - B_LPW : q) : (q < A_LPW ? q : q - A_LPW); };
+    auto load_part = [](int q) { return ORD == 0 ? q % KS : q * KS / LPS; };
+    auto issue_part = [&](int g, int part, bool more_a, bool more_b) {
 #pragma unroll
-        for (int part = 0; part < KS; ++part) issue_part(kt, buf, part);
+        for (int q = 0; q < LPS; ++q) {
+            if (load_part(q) != part) continue;
+            if (load_is_a(q)) {
+                if (more_a) issue_a(g + NSA - 1, load_idx(q));
+            } else {
+                if (more_b) issue_b(g + NSB - 1, load_idx(q));
+            }
+        }
     };
     // ---- LDS byte offsets of the operand rows this lane feeds to the MFMAs ----
     const int fr = lane & 31, fq = lane >> 5;
@@ -377,16 +396,17 @@ __global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
         int r;
         if (GATED) r = (j < TNO) ? (wn * WNO + j * 32 + fr) : (NO + wn * WNO + (j - TNO) * 32 + fr);
         else r = wn * WNO + j * 32 + fr;
-        b_row[j] = BM * ROWB + r * ROWB;
+        b_row[j] = B_BASE + r * ROWB;
     }
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) k_off[kk] = ((kk * 2 + fq) ^ fsw) << 4;
 
     const int nk_ = K / PBK;
-    // Software pipeline.  Global side: stages kt+1 .. kt+NSTAGE-1 are in flight while stage kt is
-    // multiplied.  LDS side: the operand fragments of k-slice kk+1 are read while the MFMAs of slice
-    // kk run; the last slice of a stage runs after the barrier that hands over the next stage, under
-    // the reads of that stage's first slice.
+    // Software pipeline.  Global side: activation stages g+1 .. g+NSA-1 and weight stages g+1 ..
+    // g+NSB-1 are in flight while stage g is multiplied (the weight ring may be one stage deeper: the
+    // weights are what comes from HBM).  LDS side: the operand fragments of k-slice kk+1 are read while
+    // the MFMAs of slice kk run; the last slice of a stage runs after the barrier that hands over the
+    // next stage, under the reads of that stage's first slice.
     // The body is instantiated for the number TMV of row blocks this wave really has (0..TM), so the
     // hot loop is straight-line code; a wave with no row block still loads and synchronises.
     auto run = [&](auto tmv_const) {
@@ -400,14 +420,16 @@ __global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
         bf16x8_t af[2][TMA], bfr[2][TN];
-        auto read_frags = [&](const char* base, int kk, int set) {
+        auto read_frags = [&](int g, int kk, int set) {
             if (TMV == 0) return;
+            const char* base_a = smem + (g % NSA) * A_SLOT;
+            const char* base_b = smem + (g % NSB) * B_SLOT;
 #pragma unroll
             for (int i = 0; i < TMV; ++i)
-                af[set][i] = *reinterpret_cast<const bf16x8_t*>(base + a_row[i] + k_off[kk]);
+                af[set][i] = *reinterpret_cast<const bf16x8_t*>(base_a + a_row[i] + k_off[kk]);
 #pragma unroll
             for (int j = 0; j < TN; ++j)
-                bfr[set][j] = *reinterpret_cast<const bf16x8_t*>(base + b_row[j] + k_off[kk]);
+                bfr[set][j] = *reinterpret_cast<const bf16x8_t*>(base_b + b_row[j] + k_off[kk]);
         };
         auto mfma_set = [&](int set) {
 #pragma unroll
@@ -419,16 +441,24 @@ __global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[set][j], af[set][i], acc[i][j], 0, 0, 0);
         };
 
+        // prologue: stage 0 of both operands first, then the rest of what the rings hold
 #pragma unroll
-        for (int st = 0; st < NSTAGE - 1; ++st)
-            if (st < nk_) issue_stage(st, st);
-        if (nk_ >= NSTAGE - 1) wait_vmcnt<WAIT_MAIN>();
+        for (int st = 0; st < NSMAX - 1; ++st) {
+            if (st < NSA - 1 && st < nk_)
+#pragma unroll
+                for (int p = 0; p < A_LPW; ++p) issue_a(st, p);
+            if (st < NSB - 1 && st < nk_)
+#pragma unroll
+                for (int p = 0; p < B_LPW; ++p) issue_b(st, p);
+        }
+        if (nk_ >= NSMAX - 1) wait_vmcnt<WAIT_FIRST>();
         else wait_vmcnt<0>();
         block_barrier();
-        read_frags(smem, 0, 0);
-        // One k-step.  MORE: stage kt+NSTAGE-1 exists and is loaded (in KS parts, between the MFMAs)
-        // into the buffer stage kt-1 used, free since the last barrier.  NEXT: stage kt+1 exists; it is
-        // waited for and handed over by the barrier before the last slice of this stage is multiplied.
+        read_frags(0, 0, 0);
+        // One k-step.  MORE_A / MORE_B: activation stage g+NSA-1 / weight stage g+NSB-1 exists and is
+        // loaded (in parts, between the MFMAs) into the slot stage g-1 used, free since the last
+        // barrier.  NEXT: stage g+1 exists; it is waited for and handed over by the barrier before the
+        // last slice of this stage is multiplied.
         // Ask the scheduler to issue the LDS reads and the global loads of a region one by one between
         // its MFMAs (they then execute in the shadow of the matrix pipe) instead of in a clump.
         auto interleave = [](int n_ds, int n_vmem, int n_mfma) {
@@ -447,43 +477,46 @@ __global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
                 }
             }
         };
-        auto parts_in = [](int part) {
+        auto parts_in = [&](int part, bool more_a, bool more_b) {
             int n = 0;
-            for (int p = 0; p < LPS; ++p) n += (p % KS == part);
+            for (int q = 0; q < LPS; ++q)
+                if (load_part(q) == part) n += load_is_a(q) ? more_a : more_b;
             return n;
         };
-        auto step = [&](int kt, auto more_c, auto next_c, auto drain_c) {
-            constexpr bool MORE = decltype(more_c)::value, NEXT = decltype(next_c)::value;
-            constexpr bool DRAIN = decltype(drain_c)::value;
-            const char* base = smem + (kt % NSTAGE) * STAGE;
-            const int nxt = kt + NSTAGE - 1;
-            const int nxt_buf = nxt % NSTAGE;
+        auto step = [&](int g, auto more_a_c, auto more_b_c, auto next_c) {
+            constexpr bool MORE_A = decltype(more_a_c)::value, MORE_B = decltype(more_b_c)::value;
+            constexpr bool NEXT = decltype(next_c)::value;
 #pragma unroll
             for (int kk = 0; kk < KS - 1; ++kk) {
-                read_frags(base, kk + 1, (kk + 1) & 1);
-                if (MORE) issue_part(nxt, nxt_buf, kk);
+                read_frags(g, kk + 1, (kk + 1) & 1);
+                issue_part(g, kk, MORE_A, MORE_B);
                 mfma_set(kk & 1);
-                interleave(TMV > 0 ? TMV + TN : 0, MORE ? parts_in(kk) : 0, TMV * TN);
+                interleave(TMV > 0 ? TMV + TN : 0, parts_in(kk, MORE_A, MORE_B), TMV * TN);
             }
-            if (MORE) issue_part(nxt, nxt_buf, KS - 1);
+            issue_part(g, KS - 1, MORE_A, MORE_B);
             if (NEXT) {
-                if (DRAIN) wait_vmcnt<0>();
-                else wait_vmcnt<WAIT_MAIN>();
-                // all of this wave's reads of stage kt have returned before its buffer may be refilled
+                if (MORE_A && MORE_B) wait_vmcnt<WAIT_MAIN>();
+                else wait_vmcnt<0>();        // the pipeline drains: wait for everything
+                // all of this wave's reads of stage g have returned before its slots may be refilled
                 wait_lds_reads();
                 block_barrier();
-                read_frags(smem + ((kt + 1) % NSTAGE) * STAGE, 0, 0);
+                read_frags(g + 1, 0, 0);
             }
             mfma_set((KS - 1) & 1);
             interleave(NEXT && TMV > 0 ? TMV + TN : 0, 0, TMV * TN);
         };
         using T = std::true_type;
         using F = std::false_type;
-        const int n_main = nk_ - (NSTAGE - 1) > 0 ? nk_ - (NSTAGE - 1) : 0;   // steps that still start a new stage
-        int kt = 0;
-        for (; kt < n_main; ++kt) step(kt, T{}, T{}, F{});
-        for (; kt < nk_ - 1; ++kt) step(kt, F{}, T{}, T{});     // pipeline drains: wait for everything
-        step(kt, F{}, F{}, F{});
+        const int n_main = nk_ - (NSMAX - 1) > 0 ? nk_ - (NSMAX - 1) : 0;   // steps that still start both loads
+        int g = 0;
+        for (; g < n_main; ++g) step(g, T{}, T{}, T{});
+        for (; g < nk_ - 1; ++g) {
+            // only the shallower ring may still have a stage to fetch
+            if (NSA < NSB && g + NSA - 1 < nk_) step(g, T{}, F{}, T{});
+            else if (NSB < NSA && g + NSB - 1 < nk_) step(g, F{}, T{}, T{});
+            else step(g, F{}, F{}, T{});
+        }
+        step(g, F{}, F{}, F{});
 
 #pragma unroll
         for (int i = 0; i < TMV; ++i) {
@@ -568,8 +601,8 @@ static Variant pick_variant(int64_t A, int E, int K)
     static const char* force = getenv("MOE_FFN_VARIANT");   // tuning aid: "tile128", "small", "big"
     Variant v;
     const double mean_rows = (double)A / (double)E;
-    if (mean_rows <= 64.0) v = V_PIPE_SMALL;   // weight streaming: 64-row tiles, 3 stages of 64 k-values
-    else v = V_PIPE_BIG;                       // up to 256-row tiles, 4 stages of 32 k-values
+    if (mean_rows <= 64.0) v = V_PIPE_SMALL;   // weight streaming: 64 x 128 tiles, 3 stages of 64 k-values
+    else v = V_PIPE_BIG;                       // up to 256-row tiles, 2 + 3 stages of 64 k-values
     if (force) {
         if (!strcmp(force, "tile128")) v = V_TILE128;
         if (!strcmp(force, "small")) v = V_PIPE_SMALL;
@@ -602,15 +635,15 @@ static hipError_t launch_tile(RowSrc X, int ldx, const int32_t* row_map, int map
     return hipGetLastError();
 }
 
-template <int RBM, int BN, int WM, int NSTAGE, int PBK, int MINW, int NW, bool GATED>
+template <int RBM, int BN, int WM, int NSA, int NSB, int PBK, int MINW, int NW, int ORD, bool GATED>
 static hipError_t launch_pipe(RowSrc X, int ldx, const int32_t* row_map, int map_div, const int32_t* offsets,
                               int E, int64_t A, const bf16_t* W, int64_t w_expert_stride, int N, int K, bf16_t* Out,
                               int ldo, hipStream_t s)
 {
     constexpr int BM = RBM * 32;
     constexpr int NO = GATED ? BN / 2 : BN;
-    const size_t lds_bytes = (size_t)NSTAGE * (BM + BN) * PBK * 2;
-    auto kern = grouped_gemm_bf16_pipe_kernel<RBM, BN, WM, NSTAGE, PBK, MINW, NW, GATED>;
+    const size_t lds_bytes = ((size_t)NSA * BM + (size_t)NSB * BN) * PBK * 2;
+    auto kern = grouped_gemm_bf16_pipe_kernel<RBM, BN, WM, NSA, NSB, PBK, MINW, NW, ORD, GATED>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -631,13 +664,15 @@ static hipError_t launch_bf16(RowSrc X, int ldx, const int32_t* row_map, int map
                               int E, int64_t A, const bf16_t* W, int64_t w_expert_stride, int N, int K, bf16_t* Out,
                               int ldo, hipStream_t s)
 {
-    // both pipelined variants: 8 waves (2 per SIMD, so one wave's barrier / LDS waits are covered by the
-    // other's MFMAs), 2 (rows) x 4 (columns), 256 weight rows per block
+    // weight streaming: 64 x 128 tiles, 4 waves, 72 KB of LDS: two blocks share a compute unit, so one
+    // block's prologue and epilogue are covered by the other's loads, and the many small tiles balance
+    // well over the chip.  compute bound: 256 x 256 tiles, 8 waves (2 per SIMD: one wave's barrier and
+    // LDS waits are covered by the other's MFMAs), 2 (rows) x 4 (columns).
     switch (pick_variant(A, E, K)) {
         case V_PIPE_SMALL:
-            return launch_pipe<2, 256, 2, 3, 64, 2, 8, GATED>(X, ldx, row_map, map_div, offsets, E, A, W, w_expert_stride, N, K, Out, ldo, s);
+            return launch_pipe<2, 128, 2, 3, 3, 64, 2, 4, 0, GATED>(X, ldx, row_map, map_div, offsets, E, A, W, w_expert_stride, N, K, Out, ldo, s);
         case V_PIPE_BIG:
-            return launch_pipe<8, 256, 2, 4, 32, 2, 8, GATED>(X, ldx, row_map, map_div, offsets, E, A, W, w_expert_stride, N, K, Out, ldo, s);
+            return launch_pipe<8, 256, 2, 2, 3, 64, 2, 8, 1, GATED>(X, ldx, row_map, map_div, offsets, E, A, W, w_expert_stride, N, K, Out, ldo, s);
         default:
             return launch_tile<128, 128, GATED>(X, ldx, row_map, map_div, offsets, E, A, W, w_expert_stride, N, K, Out,
                                                 ldo, s);
@@ -675,8 +710,8 @@ const char* ffn_variant_name(int dtype, int64_t A, int E, int H, int I)
     (void)I;
     if (dtype != MOE_BF16) return "grouped_gemm_f32_kernel<gated>";
     switch (pick_variant(A, E, H)) {
-        case V_PIPE_SMALL: return "grouped_gemm_bf16_pipe_kernel<2,256,2,3,64,2,8,gated>";
-        case V_PIPE_BIG: return "grouped_gemm_bf16_pipe_kernel<8,256,2,4,32,2,8,gated>";
+        case V_PIPE_SMALL: return "grouped_gemm_bf16_pipe_kernel<2,128,2,3,3,64,2,4,0,gated>";
+        case V_PIPE_BIG: return "grouped_gemm_bf16_pipe_kernel<8,256,2,2,3,64,2,8,1,gated>";
         default: return "grouped_gemm_bf16_kernel<128,128,gated>";
     }
 }
