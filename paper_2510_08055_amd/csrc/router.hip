@@ -105,68 +105,190 @@ __device__ __forceinline__ bool before(double va, int ia, double vb, int ib)
     return va > vb || (va == vb && ia < ib);
 }
 
-// One wave per token.  Lane l holds logits of experts l, l+64, ...; K rounds of a wave-wide
-// arg-max, each removing the winner.  Lane j keeps the j-th winner and computes its weight.
+// One wave per token (TPW tokens one after the other).  Lane l holds logits of experts l, l+64, ...;
+// K rounds of a wave-wide arg-max, each removing the winner.  Lane j keeps the j-th winner and
+// computes its weight.  The block also counts its assignments per (permutation tile, expert) in LDS
+// and adds the non-zero bins to the global per-tile histogram: integer counts do not depend on the
+// order of the atomics, and few experts (a skewed top-2 of 8) no longer serialise on one address.
+constexpr int kTopkWaves = 8;
 template <int NPL>
-__global__ __launch_bounds__(256) void topk_kernel(const double* __restrict__ logits, int64_t n_tok, int E, int K,
-                                                   int renorm, int32_t* __restrict__ idx, float* __restrict__ w,
-                                                   int32_t* __restrict__ tile_hist)
+__global__ __launch_bounds__(kTopkWaves * 64) void topk_kernel(const double* __restrict__ logits, int64_t n_tok, int E,
+                                                               int K, int renorm, int tpw, int32_t* __restrict__ idx,
+                                                               float* __restrict__ w, int32_t* __restrict__ tile_hist)
 {
+    // a block's assignments (at most 8 waves x tpw tokens x K <= kPermTile) touch at most two tiles
+    __shared__ int32_t hist[2][kMaxExperts];
     const int lane = lane_id();
-    const int64_t t = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (t >= n_tok) return;
+    const int wave = threadIdx.x >> 6;
+    const int64_t tb0 = (int64_t)blockIdx.x * (kTopkWaves * tpw);
+    const int64_t tile0 = tb0 * K / kPermTile;
+    if (tile_hist) {
+        for (int i = threadIdx.x; i < 2 * E; i += kTopkWaves * 64) hist[i / E][i % E] = 0;
+        __syncthreads();
+    }
+    const double NEG = -__builtin_huge_val();
+    for (int it = 0; it < tpw; ++it) {
+        const int64_t t = tb0 + (int64_t)wave * tpw + it;
+        if (t >= n_tok) break;
+        double v[NPL];
+#pragma unroll
+        for (int i = 0; i < NPL; ++i) {
+            const int e = lane + 64 * i;
+            v[i] = (e < E) ? logits[t * E + e] : NEG;
+        }
+        double my_z = NEG;
+        int my_e = 0;
+        double z_max = 0.0;
+        for (int j = 0; j < K; ++j) {
+            double bv = v[0];
+            int bi = 0;
+#pragma unroll
+            for (int i = 1; i < NPL; ++i)
+                if (v[i] > bv) { bv = v[i]; bi = i; }
+            int be = lane + 64 * bi;
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) {
+                const double ov = __shfl_xor(bv, off, 64);
+                const int oe = __shfl_xor(be, off, 64);
+                if (before(ov, oe, bv, be)) { bv = ov; be = oe; }
+            }
+            if (j == 0) z_max = bv;
+            if (lane == j) { my_z = bv; my_e = be; }
+            if ((be & 63) == lane) {
+                const int slot = be >> 6;
+#pragma unroll
+                for (int i = 0; i < NPL; ++i)
+                    if (i == slot) v[i] = NEG;
+            }
+        }
+        // softmax numerator of the selected expert; denominator over all E unless renormalising
+        double p = (lane < K) ? exp(my_z - z_max) : 0.0;
+        double denom;
+        if (renorm) {
+            denom = p;
+        } else {
+            denom = 0.0;
+#pragma unroll
+            for (int i = 0; i < NPL; ++i) {
+                const int e = lane + 64 * i;
+                if (e < E) denom += exp(logits[t * E + e] - z_max);
+            }
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) denom += __shfl_xor(denom, off, 64);
+        if (lane < K) {
+            idx[t * K + lane] = my_e;
+            w[t * K + lane] = (float)(p / denom);
+            if (tile_hist) atomicAdd(&hist[(t * K + lane) / kPermTile - tile0][my_e], 1);
+        }
+    }
+    if (tile_hist) {
+        __syncthreads();
+        for (int i = threadIdx.x; i < 2 * E; i += kTopkWaves * 64) {
+            const int c = hist[i / E][i % E];
+            if (c) atomicAdd(&tile_hist[(tile0 + i / E) * E + i % E], c);
+        }
+    }
+}
+
+// ----------------------------------------------------------------------------------------------
+// Top-k for K <= 16: one token per 16-lane row, four tokens per wave.  Lane c of a row holds the
+// logits of experts c, c+16, c+32, ...; a round takes the lane's best, then an all-reduce over the
+// row in four DPP steps (lane ^ 1, lane ^ 2, mirror within 8, mirror within 16: register-to-register
+// moves, no LDS), under the same total order (logit desc, index asc), so every lane of the row ends
+// with the same winner.  Lane j of the row keeps winner j.
+// ----------------------------------------------------------------------------------------------
+template <int CTRL> __device__ __forceinline__ int dpp_mov(int v)
+{
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, true);
+}
+template <int CTRL> __device__ __forceinline__ double dpp_mov(double v)
+{
+    return __hiloint2double(dpp_mov<CTRL>(__double2hiint(v)), dpp_mov<CTRL>(__double2loint(v)));
+}
+constexpr int kDppXor1 = 0xB1, kDppXor2 = 0x4E, kDppHalfMirror = 0x141, kDppMirror = 0x140;
+
+template <int CTRL> __device__ __forceinline__ void row_best_step(double& bv, int& be)
+{
+    const double ov = dpp_mov<CTRL>(bv);
+    const int oe = dpp_mov<CTRL>(be);
+    if (before(ov, oe, bv, be)) { bv = ov; be = oe; }
+}
+template <int CTRL> __device__ __forceinline__ double row_sum_step(double v) { return v + dpp_mov<CTRL>(v); }
+
+template <int NPL>   // logits per lane: experts c + 16 i, i < NPL
+__global__ __launch_bounds__(kTopkWaves * 64) void topk_rows_kernel(const double* __restrict__ logits, int64_t n_tok,
+                                                                    int E, int K, int renorm, int32_t* __restrict__ idx,
+                                                                    float* __restrict__ w,
+                                                                    int32_t* __restrict__ tile_hist)
+{
+    // a block's assignments (32 tokens x K <= 512) touch at most two permutation tiles
+    __shared__ int32_t hist[2][kMaxExperts];
+    const int lane = lane_id();
+    const int wave = threadIdx.x >> 6;
+    const int c = lane & 15;
+    const int64_t tb0 = (int64_t)blockIdx.x * (kTopkWaves * 4);
+    const int64_t tile0 = tb0 * K / kPermTile;
+    if (tile_hist) {
+        for (int i = threadIdx.x; i < 2 * E; i += kTopkWaves * 64) hist[i / E][i % E] = 0;
+        __syncthreads();
+    }
+    const int64_t t = tb0 + wave * 4 + (lane >> 4);
+    const bool live = t < n_tok;
+    const int64_t tl = live ? t : n_tok - 1;      // rows past the end work on a copy of the last token, store nothing
     const double NEG = -__builtin_huge_val();
     double v[NPL];
 #pragma unroll
     for (int i = 0; i < NPL; ++i) {
-        const int e = lane + 64 * i;
-        v[i] = (e < E) ? logits[t * E + e] : NEG;
+        const int e = c + 16 * i;
+        v[i] = (e < E) ? logits[tl * E + e] : NEG;
     }
-    double my_z = NEG;
+    double esum = 0.0;      // only without renormalisation: this lane's share of sum_e exp(z_e - z_max)
+    double my_z = NEG, z_max = 0.0;
     int my_e = 0;
-    double z_max = 0.0;
     for (int j = 0; j < K; ++j) {
         double bv = v[0];
-        int bi = 0;
+        int be = c;
 #pragma unroll
         for (int i = 1; i < NPL; ++i)
-            if (v[i] > bv) { bv = v[i]; bi = i; }
-        int be = lane + 64 * bi;
+            if (v[i] > bv) { bv = v[i]; be = c + 16 * i; }     // equal values: the lower index stays
+        row_best_step<kDppXor1>(bv, be);
+        row_best_step<kDppXor2>(bv, be);
+        row_best_step<kDppHalfMirror>(bv, be);
+        row_best_step<kDppMirror>(bv, be);
+        if (j == 0) {
+            z_max = bv;
+            if (!renorm) {
 #pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) {
-            const double ov = __shfl_xor(bv, off, 64);
-            const int oe = __shfl_xor(be, off, 64);
-            if (before(ov, oe, bv, be)) { bv = ov; be = oe; }
+                for (int i = 0; i < NPL; ++i)
+                    if (c + 16 * i < E) esum += exp(v[i] - z_max);
+            }
         }
-        if (j == 0) z_max = bv;
-        if (lane == j) { my_z = bv; my_e = be; }
-        if ((be & 63) == lane) {
-            const int slot = be >> 6;
+        if (c == j) { my_z = bv; my_e = be; }
+        if ((be & 15) == c) {
+            const int slot = be >> 4;
 #pragma unroll
             for (int i = 0; i < NPL; ++i)
                 if (i == slot) v[i] = NEG;
         }
     }
-    // softmax numerator of the selected expert; denominator over all E unless renormalising
-    double p = (lane < K) ? exp(my_z - z_max) : 0.0;
-    double denom;
-    if (renorm) {
-        denom = p;
-    } else {
-        denom = 0.0;
-#pragma unroll
-        for (int i = 0; i < NPL; ++i) {
-            const int e = lane + 64 * i;
-            if (e < E) denom += exp(logits[t * E + e] - z_max);
-        }
+    const double p = (c < K) ? exp(my_z - z_max) : 0.0;
+    double denom = renorm ? p : esum;
+    denom = row_sum_step<kDppXor1>(denom);
+    denom = row_sum_step<kDppXor2>(denom);
+    denom = row_sum_step<kDppHalfMirror>(denom);
+    denom = row_sum_step<kDppMirror>(denom);
+    if (live && c < K) {
+        idx[t * K + c] = my_e;
+        w[t * K + c] = (float)(p / denom);
+        if (tile_hist) atomicAdd(&hist[(t * K + c) / kPermTile - tile0][my_e], 1);
     }
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) denom += __shfl_xor(denom, off, 64);
-    if (lane < K) {
-        idx[t * K + lane] = my_e;
-        w[t * K + lane] = (float)(p / denom);
-        // per-tile expert histogram for the permutation (integer atomics: the counts do not depend on order)
-        if (tile_hist) atomicAdd(&tile_hist[((t * K + lane) / kPermTile) * E + my_e], 1);
+    if (tile_hist) {
+        __syncthreads();
+        for (int i = threadIdx.x; i < 2 * E; i += kTopkWaves * 64) {
+            const int cnt = hist[i / E][i % E];
+            if (cnt) atomicAdd(&tile_hist[(tile0 + i / E) * E + i % E], cnt);
+        }
     }
 }
 
@@ -186,12 +308,27 @@ hipError_t launch_router_logits(int dtype, RowSrc x, int64_t T, int H, const voi
 hipError_t launch_topk(const double* logits, int64_t T, int E, int K, int renorm, int32_t* idx, float* w,
                        int32_t* tile_hist, hipStream_t s)
 {
-    const unsigned grid = (unsigned)((T + 3) / 4);
+    if (K <= 16) {
+        const unsigned grid = (unsigned)((T + kTopkWaves * 4 - 1) / (kTopkWaves * 4));
+        const int npl = (E + 15) / 16;
+#define MOE_TOPK_ROWS(N) topk_rows_kernel<N><<<grid, kTopkWaves * 64, 0, s>>>(logits, T, E, K, renorm, idx, w, tile_hist)
+        if (npl <= 1) MOE_TOPK_ROWS(1);
+        else if (npl <= 2) MOE_TOPK_ROWS(2);
+        else if (npl <= 4) MOE_TOPK_ROWS(4);
+        else if (npl <= 8) MOE_TOPK_ROWS(8);
+        else if (npl <= 16) MOE_TOPK_ROWS(16);
+        else MOE_TOPK_ROWS(32);
+#undef MOE_TOPK_ROWS
+        return hipGetLastError();
+    }
+    // more than 16 winners per token: one token per wave, lane j keeps winner j
+    const int tpw = T <= 2048 ? 1 : 4;
+    const unsigned grid = (unsigned)((T + kTopkWaves * tpw - 1) / (kTopkWaves * tpw));
     const int npl = (E + 63) / 64;
-    if (npl <= 1) topk_kernel<1><<<grid, 256, 0, s>>>(logits, T, E, K, renorm, idx, w, tile_hist);
-    else if (npl <= 2) topk_kernel<2><<<grid, 256, 0, s>>>(logits, T, E, K, renorm, idx, w, tile_hist);
-    else if (npl <= 4) topk_kernel<4><<<grid, 256, 0, s>>>(logits, T, E, K, renorm, idx, w, tile_hist);
-    else topk_kernel<8><<<grid, 256, 0, s>>>(logits, T, E, K, renorm, idx, w, tile_hist);
+    if (npl <= 1) topk_kernel<1><<<grid, kTopkWaves * 64, 0, s>>>(logits, T, E, K, renorm, tpw, idx, w, tile_hist);
+    else if (npl <= 2) topk_kernel<2><<<grid, kTopkWaves * 64, 0, s>>>(logits, T, E, K, renorm, tpw, idx, w, tile_hist);
+    else if (npl <= 4) topk_kernel<4><<<grid, kTopkWaves * 64, 0, s>>>(logits, T, E, K, renorm, tpw, idx, w, tile_hist);
+    else topk_kernel<8><<<grid, kTopkWaves * 64, 0, s>>>(logits, T, E, K, renorm, tpw, idx, w, tile_hist);
     return hipGetLastError();
 }
 

@@ -33,6 +33,9 @@ def dev_layer(layer):
     (19, 64, 1, 1, "bf16", False),
     (40, 128, 200, 5, "bf16", False),       # E not a multiple of 16 or 64
     (5, 72, 16, 16, "f32", False),          # K = E, H not a multiple of 32
+    (45, 128, 300, 12, "bf16", True),       # more than 256 experts: 32 logits per lane in the 16-lane-row kernel
+    (30, 128, 64, 24, "bf16", True),        # K > 16: the one-token-per-wave kernel
+    (9, 256, 512, 64, "bf16", False),       # the largest E and K the library takes
 ])
 def test_router_topk_bit_exact(gpu_lib, T, H, E, K, dtype, bias):
     w = inputs.Workload("r", H=H, E=E, K=K, I=64, n_layers=1, D=0, P=T, dtype=dtype, seed=T + E)
