@@ -144,13 +144,27 @@ __global__ __launch_bounds__(kPermThreads) void permute_scatter_kernel(
         if (valid && (63 - __clzll(peers)) == lane) wave_cnt[wave][e] += __popcll(peers);
         __builtin_amdgcn_wave_barrier();
     }
-    __syncthreads();   // the scatter below adds the counts of the waves in front of this one
+    __syncthreads();
+    // wave_cnt[w][e] becomes the first permuted row of wave w's assignments to expert e: this tile's
+    // start inside the expert plus the counts of the waves in front (one pass per expert, instead of
+    // every assignment adding up the waves in front of it)
+    for (int e = tid; e < E; e += kPermThreads) {
+        int c[kPermWaves];
+#pragma unroll
+        for (int wv = 0; wv < kPermWaves; ++wv) c[wv] = wave_cnt[wv][e];
+        int run = start[e];
+#pragma unroll
+        for (int wv = 0; wv < kPermWaves; ++wv) {
+            wave_cnt[wv][e] = run;
+            run += c[wv];
+        }
+    }
+    __syncthreads();
 #pragma unroll
     for (int r = 0; r < kPermRounds; ++r) {
         const int e = my_e[r];
         if (e < 0) continue;
-        int pos = start[e] + my_rank[r];
-        for (int wv = 0; wv < wave; ++wv) pos += wave_cnt[wv][e];
+        const int pos = wave_cnt[wave][e] + my_rank[r];
         const int64_t f = base + (int64_t)wave * (kPermRounds * 64) + r * 64 + lane;
         perm[pos] = (int32_t)f;
         inv[f] = pos;
