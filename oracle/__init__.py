@@ -210,3 +210,57 @@ def group_forward(layers, x_decode, x_prefill, k, schedule, chunk=0, renormalize
     if want_trace:
         return y_decode, y_prefill, c, trace
     return y_decode, y_prefill, c
+
+
+def num_layer_groups(prompt_len, n_layers, granule=512) -> int:
+    """N_lg(L) = max(1, ceil(L / granule)), at most n_layers (0 for invalid arguments)."""
+    return int(lib().orc_num_layer_groups(ctypes.c_int64(prompt_len), int(n_layers), ctypes.c_int64(granule)))
+
+
+def layer_groups(n_layers, n_groups):
+    """first[0..n_groups]: group g holds layers first[g] .. first[g+1]-1."""
+    first = np.zeros(max(n_groups, 0) + 1, dtype=np.int32)
+    _check(lib().orc_layer_groups(int(n_layers), int(n_groups), _p(first)), "layer_groups")
+    return first
+
+
+def stack_forward(layers, x_decode, x_prefill, k, chunk=0, n_groups=0, granule=512, renormalize=True,
+                  residual=True, act_dtype=None):
+    """A whole layer stack under the one-group-per-iteration rule, the prompt cut into slices of `chunk`
+    tokens (0: one slice), each slice crossing n_groups layer groups (0: the group-count rule with `granule`).
+    Arguments as for group_forward.  Returns y_decode [D,H] f64, y_prefill [P,H] f64, Counters.
+    """
+    n = len(layers)
+    Wr = [_c(l["w_router"]) for l in layers]
+    Wgu = [_c(l["w_gate_up"]) for l in layers]
+    Wd = [_c(l["w_down"]) for l in layers]
+    Bs = [None if l.get("router_bias") is None else _c(l["router_bias"], np.float32) for l in layers]
+    E, H = Wr[0].shape
+    I = Wd[0].shape[2]
+    wdt = _dt(Wr[0])
+    for a, b_, c_ in zip(Wr, Wgu, Wd):
+        assert a.shape == (E, H) and b_.shape == (E, 2 * I, H) and c_.shape == (E, H, I)
+        assert _dt(a) == wdt and _dt(b_) == wdt and _dt(c_) == wdt
+    x_decode, x_prefill = _c(x_decode), _c(x_prefill)
+    D, P = x_decode.shape[0], x_prefill.shape[0]
+    if D and P:
+        assert x_decode.dtype == x_prefill.dtype
+    xdt = _dt(x_decode if D else x_prefill)
+    if act_dtype is None:
+        act_dtype = xdt
+    VP = ctypes.c_void_p * n
+    wr_arr = VP(*[a.ctypes.data for a in Wr])
+    gu_arr = VP(*[a.ctypes.data for a in Wgu])
+    d_arr = VP(*[a.ctypes.data for a in Wd])
+    b_arr = VP(*[None if b_ is None else b_.ctypes.data for b_ in Bs])
+    y_decode = np.zeros((D, H), dtype=np.float64)
+    y_prefill = np.zeros((P, H), dtype=np.float64)
+    ctr = _Counters()
+    rc = lib().orc_stack_forward(wr_arr, b_arr, gu_arr, d_arr, wdt, n, ctypes.c_int64(H), E, k,
+                                 ctypes.c_int64(I), int(bool(renormalize)), int(bool(residual)),
+                                 int(act_dtype), _p(x_decode), ctypes.c_int64(D), _p(x_prefill),
+                                 ctypes.c_int64(P), xdt, ctypes.c_int64(chunk), int(n_groups),
+                                 ctypes.c_int64(granule), _p(y_decode), _p(y_prefill), ctypes.byref(ctr))
+    _check(rc, "stack_forward")
+    return y_decode, y_prefill, Counters(ctr.expert_bytes, ctr.router_bytes, ctr.active_experts_total,
+                                         ctr.tokens_processed, ctr.iterations, ctr.layer_passes)

@@ -20,6 +20,10 @@
  *     tokens riding along): Sec. 4.1, Sec. 4.2, Fig. 1 (lower).
  *   - Expert-weight load bytes (an expert's parameters are counted every time
  *     they are brought in for execution, prefill or decode): Sec. 5.4.
+ *   - A whole layer stack cut into contiguous layer groups, one group per
+ *     iteration doing prefill and decode while the others do decode only:
+ *     Sec. 4.1, Sec. 4.2; combined with chunking along the tokens: Sec. 4.3;
+ *     the number of groups for a prompt length: Sec. 4.4.
  *
  * The paper does not print the layer's arithmetic.  The readings used here:
  * selection on raw logits, ties to the lower expert index, selected experts
@@ -374,5 +378,142 @@ int orc_group_forward(const void *const *Wr, const float *const *bias,
     }
     if (ctr) *ctr = c;
     free(xb); free(yb); free(idx); free(seen);
+    return status;
+}
+
+
+/* ---------------------------------------------------------------------------
+ * Whole stack: layer groups, the group-count rule and the one-group-per-
+ * iteration schedule.
+ * ------------------------------------------------------------------------ */
+
+/*
+ * Sec. 4.4: the number of layer groups is chosen so that the prefill work of one
+ * iteration matches a chunk of `granule` tokens: N_lg(L) = max(1, ceil(L / granule)).
+ * The paper's own worked values, granule 512: L = 8192 -> 16, L = 512 -> 1.
+ * (Reading: a group holds at least one layer, so the count is capped at n_layers.)
+ */
+int orc_num_layer_groups(int64_t L, int n_layers, int64_t granule)
+{
+    if (L < 0 || n_layers <= 0 || granule <= 0) return 0;
+    int64_t n = L / granule + (L % granule != 0);
+    if (n < 1) n = 1;
+    if (n > n_layers) n = n_layers;
+    return (int)n;
+}
+
+/*
+ * Sec. 4.1: the stack is cut vertically into contiguous layer groups.  The paper does not
+ * say how a remainder is spread; reading: sizes differ by at most one, larger groups first.
+ * first[g] is the first layer of group g, first[n_groups] = n_layers.
+ */
+int orc_layer_groups(int n_layers, int n_groups, int32_t *first)
+{
+    if (!first || n_groups < 1 || n_groups > n_layers) return ORC_ERR_ARG;
+    int at = 0;
+    for (int g = 0; g < n_groups; ++g) {
+        first[g] = at;
+        at += n_layers / n_groups + (g < n_layers % n_groups ? 1 : 0);
+    }
+    first[n_groups] = at;
+    return ORC_OK;
+}
+
+static double round_act(double v, int act_dt)
+{
+    return (act_dt == ORC_BF16) ? orc_round_bf16(v) : (act_dt == ORC_F32) ? orc_round_f32(v) : v;
+}
+
+/*
+ * The stack under the one-group-per-iteration rule (Sec. 4.1-4.2), with the prompt cut into
+ * slices of `chunk` tokens (Sec. 4.3; chunk = 0: the whole prompt is one slice).  For a slice
+ * the stack has G groups (n_groups, or the rule of Sec. 4.4 applied to the slice length when
+ * n_groups = 0) and G iterations run.  In iteration g:
+ *   - the decode rows start from x_decode and cross ALL groups in layer order (decode is never
+ *     blocked: every iteration includes decode work across all layer groups);
+ *   - group g, the designated one, also processes the slice's rows, which it takes in the state
+ *     group g-1 left them in the iteration before; the other groups do decode only.
+ * After G iterations the slice has crossed every layer exactly once.
+ * Between layers activations are rounded to act_dt (what a GPU keeps in memory); the outputs of
+ * the stack's last layer are returned unrounded.  Counters as in orc_group_forward: one
+ * iteration per (slice, g); every layer pass counts the experts it activates.
+ * A call without prompt rows is one decode-only iteration.
+ */
+int orc_stack_forward(const void *const *Wr, const float *const *bias,
+                      const void *const *Wgu, const void *const *Wd, int wdt, int n_layers,
+                      int64_t H, int E, int k, int64_t I, int renorm, int residual, int act_dt,
+                      const void *x_decode, int64_t D, const void *x_prefill, int64_t P, int xdt,
+                      int64_t chunk, int n_groups, int64_t granule,
+                      double *y_decode, double *y_prefill, orc_counters *ctr)
+{
+    if (n_layers <= 0 || D < 0 || P < 0 || H <= 0 || I <= 0 || E <= 0 || k <= 0 || k > E)
+        return ORC_ERR_ARG;
+    if (chunk < 0 || n_groups < 0 || n_groups > n_layers || (n_groups == 0 && granule <= 0))
+        return ORC_ERR_ARG;
+    if (ctr) memset(ctr, 0, sizeof(*ctr));
+    if (D + P == 0) return ORC_OK;
+
+    const int64_t step = (chunk > 0 && P > 0) ? chunk : (P > 0 ? P : 1);
+    const int64_t n_slices = (P == 0) ? 1 : (P + step - 1) / step;
+    const int64_t Tmax = D + (P < step ? P : step);
+    const int sz = (wdt == ORC_BF16) ? 2 : (wdt == ORC_F32 ? 4 : 8);
+
+    double *dec = (double *)malloc(sizeof(double) * (size_t)(D * H + 1));          /* decode rows' state */
+    double *pre = (double *)malloc(sizeof(double) * (size_t)((Tmax - D) * H + 1)); /* slice rows' state */
+    double *xb = (double *)malloc(sizeof(double) * (size_t)(Tmax * H));
+    double *yb = (double *)malloc(sizeof(double) * (size_t)(Tmax * H));
+    int32_t *idx = (int32_t *)malloc(sizeof(int32_t) * (size_t)(Tmax * k));
+    int32_t *seen = (int32_t *)malloc(sizeof(int32_t) * (size_t)E);
+    int32_t *first = (int32_t *)malloc(sizeof(int32_t) * (size_t)(n_layers + 1));
+    if (!dec || !pre || !xb || !yb || !idx || !seen || !first) {
+        free(dec); free(pre); free(xb); free(yb); free(idx); free(seen); free(first);
+        return ORC_ERR_ALLOC;
+    }
+    orc_counters c;
+    memset(&c, 0, sizeof(c));
+    int status = ORC_OK;
+    for (int64_t sl = 0; sl < n_slices && status == ORC_OK; ++sl) {
+        const int64_t p0 = sl * step;
+        const int64_t pn = (P == 0) ? 0 : ((p0 + step <= P) ? step : P - p0);
+        const int G = (pn == 0) ? 1 : (n_groups > 0 ? n_groups : orc_num_layer_groups(pn, n_layers, granule));
+        status = orc_layer_groups(n_layers, G, first);
+        if (status != ORC_OK) break;
+        for (int64_t i = 0; i < pn * H; ++i) pre[i] = ld(x_prefill, xdt, p0 * H + i);
+        for (int g = 0; g < G && status == ORC_OK; ++g) {
+            for (int64_t i = 0; i < D * H; ++i) dec[i] = ld(x_decode, xdt, i);
+            for (int j = 0; j < G && status == ORC_OK; ++j) {
+                const int with_prompt = (j == g && pn > 0);
+                const int64_t T = D + (with_prompt ? pn : 0);
+                if (T == 0) continue;
+                memcpy(xb, dec, sizeof(double) * (size_t)(D * H));
+                if (with_prompt) memcpy(xb + D * H, pre, sizeof(double) * (size_t)(pn * H));
+                for (int l = first[j]; l < first[j + 1]; ++l) {
+                    status = orc_moe_layer(xb, ORC_F64, T, H, Wr[l], (bias && bias[l]) ? bias[l] : NULL,
+                                           Wgu[l], Wd[l], wdt, E, k, I, renorm, residual, yb, idx, NULL, NULL);
+                    if (status != ORC_OK) break;
+                    for (int e = 0; e < E; ++e) seen[e] = 0;
+                    for (int64_t f = 0; f < T * k; ++f) seen[idx[f]] = 1;
+                    uint64_t active = 0;
+                    for (int e = 0; e < E; ++e) active += (uint64_t)seen[e];
+                    c.active_experts_total += active;
+                    c.expert_bytes += active * 3ull * (uint64_t)H * (uint64_t)I * (uint64_t)sz;
+                    c.router_bytes += (uint64_t)E * (uint64_t)H * (uint64_t)sz;
+                    c.layer_passes += 1;
+                    const int last_of_stack = (l == n_layers - 1);
+                    for (int64_t i = 0; i < T * H; ++i) xb[i] = last_of_stack ? yb[i] : round_act(yb[i], act_dt);
+                }
+                if (status != ORC_OK) break;
+                memcpy(dec, xb, sizeof(double) * (size_t)(D * H));
+                if (with_prompt) memcpy(pre, xb + D * H, sizeof(double) * (size_t)(pn * H));
+            }
+            if (status != ORC_OK) break;
+            c.iterations += 1;
+            c.tokens_processed += (uint64_t)(D + pn);
+            if (D > 0) memcpy(y_decode, dec, sizeof(double) * (size_t)(D * H));
+        }
+        if (status == ORC_OK && pn > 0) memcpy(y_prefill + p0 * H, pre, sizeof(double) * (size_t)(pn * H));
+    }
+    if (ctr) *ctr = c;
+    free(dec); free(pre); free(xb); free(yb); free(idx); free(seen); free(first);
     return status;
 }
