@@ -150,6 +150,49 @@ moe_status moe_group_forward(moe_ctx *ctx, const moe_layer *layers, int32_t n_la
                              const void *x_decode, int64_t D, const void *x_prefill, int64_t P,
                              moe_schedule sched, void *y_decode, void *y_prefill, void *stream);
 
+/*
+ * Layer-group count for a prompt of prompt_len tokens (Sec. 4.4): N_lg(L) = max(1, ceil(L / granule)),
+ * so that the prefill work of one iteration matches a chunk of `granule` tokens (the paper uses 512:
+ * 8192 tokens -> 16 groups, 512 tokens -> 1 group); never more groups than layers.  Host arithmetic
+ * only.  Returns 0 when prompt_len < 0, n_layers <= 0 or granule <= 0.
+ */
+int32_t moe_num_layer_groups(int64_t prompt_len, int32_t n_layers, int32_t granule);
+
+/*
+ * Cut layers 0..n_layers-1 into n_groups contiguous groups (Sec. 4.1) whose sizes differ by at most
+ * one, the larger groups first: group g holds layers first_layer[g] .. first_layer[g+1]-1.
+ * first_layer is a HOST array of n_groups + 1 entries.  MOE_ERR_SHAPE unless 1 <= n_groups <= n_layers.
+ */
+moe_status moe_layer_groups(int32_t n_layers, int32_t n_groups, int32_t *first_layer);
+
+/* How a whole layer stack is scheduled (Sec. 4.1-4.4). */
+typedef struct {
+    int32_t chunk;    /* prompt tokens admitted per outer pass (Sec. 4.3); 0 = the whole prompt at once */
+    int32_t n_groups; /* layer groups; 0 = moe_num_layer_groups(slice length, n_layers, granule) */
+    int32_t granule;  /* tokens per iteration the group-count rule aims for; read only when n_groups == 0 */
+} moe_stack_schedule;
+
+/*
+ * A whole stack of n_layers MoE layers under the one-group-per-iteration rule (Sec. 4.1-4.2), combined
+ * with chunking along the tokens (Sec. 4.3).  The prompt is cut into slices of `chunk` tokens; for each
+ * slice the stack is cut into G layer groups and G iterations run.  In iteration g every group runs,
+ * in layer order, on the decode rows (which start again from x_decode in every iteration, as under
+ * moe_group_forward); group g alone also carries the slice's rows, whose state after group g-1 is kept
+ * in y_prefill from the iteration before.  After G iterations the slice has crossed every layer once.
+ *   chunk = C, n_groups = 1:            chunked prefill over the whole stack (the baseline, Sec. 2.3);
+ *   chunk = 0, n_groups = 0:            layered prefill with the group-count rule of Sec. 4.4;
+ *   chunk = 8192, n_groups = 16 (e.g.): both at once (Sec. 4.3-4.4).
+ * Every schedule computes the same function of (x_decode, x_prefill); they differ in how many times
+ * the expert weights are read, which the counters record (iterations = sum of G over the slices,
+ * layer_passes = iterations * n_layers, tokens_processed += D + slice length per iteration).
+ * y_decode [D,H], y_prefill [P,H]; neither may be the memory of its input (MOE_ERR_SHAPE).  D + slice
+ * length must not exceed the context's max_tokens.  Errors as for moe_group_forward; MOE_ERR_SCHEDULE when chunk < 0,
+ * n_groups < 0, n_groups > n_layers, or n_groups == 0 with granule <= 0.
+ */
+moe_status moe_stack_forward(moe_ctx *ctx, const moe_layer *layers, int32_t n_layers,
+                             const void *x_decode, int64_t D, const void *x_prefill, int64_t P,
+                             moe_stack_schedule sched, void *y_decode, void *y_prefill, void *stream);
+
 /* Copy the counters to host memory `out`; synchronises `stream`. */
 moe_status moe_read_counters(moe_ctx *ctx, moe_counters *out, void *stream);
 moe_status moe_reset_counters(moe_ctx *ctx, void *stream);

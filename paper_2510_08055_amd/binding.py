@@ -19,7 +19,8 @@ MOE_F32, MOE_BF16 = 0, 1
 MOE_SCHED_CHUNKED, MOE_SCHED_LAYERED = 0, 1
 
 EXPORTS = ["moe_workspace_bytes", "moe_create", "moe_destroy", "moe_router_topk", "moe_permute",
-           "moe_grouped_ffn", "moe_combine", "moe_group_forward", "moe_read_counters", "moe_reset_counters",
+           "moe_grouped_ffn", "moe_combine", "moe_group_forward", "moe_num_layer_groups", "moe_layer_groups",
+           "moe_stack_forward", "moe_read_counters", "moe_reset_counters",
            "moe_kernel_timing", "moe_read_kernel_timing", "moe_ffn_variant", "moe_status_string"]
 
 KERNELS = {"router_logits": 0, "topk": 1, "permute": 2, "gate_up": 3, "down": 4, "combine": 5}
@@ -43,6 +44,10 @@ class CLayer(ctypes.Structure):
 
 class CSchedule(ctypes.Structure):
     _fields_ = [("kind", ctypes.c_int32), ("chunk", ctypes.c_int32)]
+
+
+class CStackSchedule(ctypes.Structure):
+    _fields_ = [("chunk", ctypes.c_int32), ("n_groups", ctypes.c_int32), ("granule", ctypes.c_int32)]
 
 
 class CCounters(ctypes.Structure):
@@ -79,6 +84,9 @@ def load():
     L.moe_grouped_ffn.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp]
     L.moe_combine.argtypes = [vp, vp, vp, vp, vp, i64, vp, vp]
     L.moe_group_forward.argtypes = [vp, ctypes.POINTER(CLayer), i32, vp, i64, vp, i64, CSchedule, vp, vp, vp]
+    L.moe_num_layer_groups.argtypes = [i64, i32, i32]
+    L.moe_layer_groups.argtypes = [i32, i32, ctypes.POINTER(i32)]
+    L.moe_stack_forward.argtypes = [vp, ctypes.POINTER(CLayer), i32, vp, i64, vp, i64, CStackSchedule, vp, vp, vp]
     L.moe_read_counters.argtypes = [vp, ctypes.POINTER(CCounters), vp]
     L.moe_reset_counters.argtypes = [vp, vp]
     L.moe_kernel_timing.argtypes = [vp, ctypes.c_uint32]
@@ -89,7 +97,7 @@ def load():
     L.moe_status_string.restype = ctypes.c_char_p
     for name in EXPORTS:
         if name not in ("moe_ffn_variant", "moe_status_string"):
-            getattr(L, name).restype = ctypes.c_int
+            getattr(L, name).restype = ctypes.c_int       # moe_status, or a count for moe_num_layer_groups
     _lib = L
     return L
 
@@ -101,6 +109,20 @@ def status_string(status: int) -> str:
 def _check(status: int, what: str):
     if status != 0:
         raise MoeError(status, what)
+
+
+def moe_num_layer_groups(prompt_len: int, n_layers: int, granule: int = 512) -> int:
+    """N_lg(L) = max(1, ceil(L / granule)), at most n_layers; 0 for invalid arguments (host arithmetic)."""
+    return int(load().moe_num_layer_groups(int(prompt_len), int(n_layers), int(granule)))
+
+
+def moe_layer_groups(n_layers: int, n_groups: int):
+    """first_layer[0..n_groups]: group g holds layers first_layer[g] .. first_layer[g+1]-1."""
+    if n_groups < 0 or n_groups > 1 << 20:
+        raise MoeError(2, "moe_layer_groups")
+    out = (ctypes.c_int32 * (n_groups + 1))()
+    _check(load().moe_layer_groups(int(n_layers), int(n_groups), out), "moe_layer_groups")
+    return list(out)
 
 
 def _ptr(t: Optional[torch.Tensor]):
@@ -220,6 +242,22 @@ class Context:
                                           _ptr(x_prefill) if P else None, P, CSchedule(kind, int(chunk)),
                                           _ptr(y_decode) if D else None, _ptr(y_prefill) if P else None, _stream()),
                "moe_group_forward")
+        return y_decode, y_prefill
+
+    def moe_stack_forward(self, layers, x_decode, x_prefill, chunk=0, n_groups=0, granule=512, packed=None,
+                          y_decode=None, y_prefill=None):
+        D = 0 if x_decode is None else x_decode.shape[0]
+        P = 0 if x_prefill is None else x_prefill.shape[0]
+        arr = packed if packed is not None else self.pack_layers(layers)
+        if y_decode is None:
+            y_decode = torch.empty((D, self.H), dtype=self.dtype, device=self.device)
+        if y_prefill is None:
+            y_prefill = torch.empty((P, self.H), dtype=self.dtype, device=self.device)
+        _check(self.lib.moe_stack_forward(self._ctx, arr, len(arr), _ptr(x_decode) if D else None, D,
+                                          _ptr(x_prefill) if P else None, P,
+                                          CStackSchedule(int(chunk), int(n_groups), int(granule)),
+                                          _ptr(y_decode) if D else None, _ptr(y_prefill) if P else None, _stream()),
+               "moe_stack_forward")
         return y_decode, y_prefill
 
     def moe_read_counters(self) -> Counters:

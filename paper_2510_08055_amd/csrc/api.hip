@@ -145,6 +145,45 @@ moe_status run_layer(moe_ctx* c, const moe_layer& L, RowSrc x, int64_t T, void* 
     return dev(e);
 }
 
+// Layers [0, n) of `layers` on the batch `in` [T,H]: the first layer reads `in` where it is, the layers
+// between ping-pong through the context's two batch buffers, the last one writes rows [0,rows0) to y0
+// and the rest to y1 (either may be the memory `in` points at: a layer's output row is written by the
+// combine kernel after every read of that row).
+moe_status run_group(moe_ctx* c, const moe_layer* layers, int n, RowSrc in, int64_t T, void* y0, int64_t rows0,
+                     void* y1, hipStream_t s)
+{
+    char* cur = static_cast<char*>(c->xa);
+    char* nxt = static_cast<char*>(c->xb);
+    for (int l = 0; l < n; ++l) {
+        const RowSrc src = (l == 0) ? in : single_src(cur);
+        moe_status st;
+        if (l + 1 < n) st = run_layer(c, layers[l], src, T, nxt, T, nxt, s);
+        else st = run_layer(c, layers[l], src, T, y0, rows0, y1, s);
+        if (st != MOE_OK) return st;
+        char* t = cur; cur = nxt; nxt = t;
+        c->layer_passes += 1;
+        c->router_bytes += (uint64_t)c->cfg.E * c->cfg.H * c->esz;
+    }
+    return MOE_OK;
+}
+
+moe_status check_stack_args(const moe_ctx* ctx, const moe_layer* layers, int32_t n_layers, const void* x_decode,
+                            int64_t D, const void* x_prefill, int64_t P, const void* y_decode, const void* y_prefill)
+{
+    if (!ctx || !layers) return MOE_ERR_NULL;
+    if (n_layers <= 0 || D < 0 || P < 0) return MOE_ERR_SHAPE;
+    if ((D > 0 && (!x_decode || !y_decode)) || (P > 0 && (!x_prefill || !y_prefill))) return MOE_ERR_NULL;
+    if ((D > 0 && (misaligned(x_decode) || misaligned(y_decode))) ||
+        (P > 0 && (misaligned(x_prefill) || misaligned(y_prefill))))
+        return MOE_ERR_ALIGN;
+    for (int l = 0; l < n_layers; ++l) {
+        if (!layers[l].w_router || !layers[l].w_gate_up || !layers[l].w_down) return MOE_ERR_NULL;
+        if (misaligned(layers[l].w_router) || misaligned(layers[l].w_gate_up) || misaligned(layers[l].w_down))
+            return MOE_ERR_ALIGN;
+    }
+    return MOE_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -280,48 +319,81 @@ moe_status moe_group_forward(moe_ctx* ctx, const moe_layer* layers, int32_t n_la
     if (n_layers <= 0 || D < 0 || P < 0) return MOE_ERR_SHAPE;
     if (sched.kind != MOE_SCHED_CHUNKED && sched.kind != MOE_SCHED_LAYERED) return MOE_ERR_SCHEDULE;
     if (sched.kind == MOE_SCHED_CHUNKED && sched.chunk <= 0) return MOE_ERR_SCHEDULE;
-    if (D + P == 0) return MOE_OK;
-    if ((D > 0 && (!x_decode || !y_decode)) || (P > 0 && (!x_prefill || !y_prefill))) return MOE_ERR_NULL;
-    if ((D > 0 && (misaligned(x_decode) || misaligned(y_decode))) ||
-        (P > 0 && (misaligned(x_prefill) || misaligned(y_prefill))))
-        return MOE_ERR_ALIGN;
-    for (int l = 0; l < n_layers; ++l) {
-        if (!layers[l].w_router || !layers[l].w_gate_up || !layers[l].w_down) return MOE_ERR_NULL;
-        if (misaligned(layers[l].w_router) || misaligned(layers[l].w_gate_up) || misaligned(layers[l].w_down))
-            return MOE_ERR_ALIGN;
+    // one group that holds every layer: each iteration sends [decode; slice] through all of them
+    moe_stack_schedule st;
+    st.chunk = sched.kind == MOE_SCHED_CHUNKED ? sched.chunk : 0;
+    st.n_groups = 1;
+    st.granule = 0;
+    return moe_stack_forward(ctx, layers, n_layers, x_decode, D, x_prefill, P, st, y_decode, y_prefill, stream);
+}
+
+int32_t moe_num_layer_groups(int64_t prompt_len, int32_t n_layers, int32_t granule)
+{
+    if (prompt_len < 0 || n_layers <= 0 || granule <= 0) return 0;
+    int64_t n = (prompt_len + granule - 1) / granule;
+    if (n < 1) n = 1;
+    if (n > n_layers) n = n_layers;
+    return (int32_t)n;
+}
+
+moe_status moe_layer_groups(int32_t n_layers, int32_t n_groups, int32_t* first_layer)
+{
+    if (!first_layer) return MOE_ERR_NULL;
+    if (n_groups < 1 || n_groups > n_layers) return MOE_ERR_SHAPE;
+    const int32_t q = n_layers / n_groups, r = n_layers % n_groups;
+    int32_t at = 0;
+    for (int32_t g = 0; g < n_groups; ++g) {
+        first_layer[g] = at;
+        at += q + (g < r ? 1 : 0);
     }
-    const int64_t step = (sched.kind == MOE_SCHED_LAYERED || P == 0) ? (P > 0 ? P : 1) : (int64_t)sched.chunk;
-    const int64_t n_iter = (P == 0) ? 1 : (P + step - 1) / step;
+    first_layer[n_groups] = at;
+    return MOE_OK;
+}
+
+moe_status moe_stack_forward(moe_ctx* ctx, const moe_layer* layers, int32_t n_layers, const void* x_decode,
+                             int64_t D, const void* x_prefill, int64_t P, moe_stack_schedule sched, void* y_decode,
+                             void* y_prefill, void* stream)
+{
+    moe_status st = check_stack_args(ctx, layers, n_layers, x_decode, D, x_prefill, P, y_decode, y_prefill);
+    if (st != MOE_OK) return st;
+    if (sched.chunk < 0 || sched.n_groups < 0 || sched.n_groups > n_layers) return MOE_ERR_SCHEDULE;
+    if (sched.n_groups == 0 && sched.granule <= 0) return MOE_ERR_SCHEDULE;
+    if (D + P == 0) return MOE_OK;
+    if ((P > 0 && x_prefill == y_prefill) || (D > 0 && x_decode == y_decode)) return MOE_ERR_SHAPE;
+    const int64_t step = (sched.chunk > 0 && P > 0) ? (int64_t)sched.chunk : (P > 0 ? P : 1);
+    const int64_t n_slices = (P == 0) ? 1 : (P + step - 1) / step;
     if (D + (P < step ? P : step) > ctx->max_tokens) return MOE_ERR_SHAPE;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const moe_config& g = ctx->cfg;
-    const size_t row_bytes = (size_t)g.H * ctx->esz;
-    for (int64_t it = 0; it < n_iter; ++it) {
-        const int64_t p0 = it * step;
+    const size_t row_bytes = (size_t)ctx->cfg.H * ctx->esz;
+    std::vector<int32_t> first((size_t)n_layers + 1);
+    for (int64_t sl = 0; sl < n_slices; ++sl) {
+        const int64_t p0 = sl * step;
         const int64_t pn = (P == 0) ? 0 : ((p0 + step <= P) ? step : P - p0);
-        const int64_t T = D + pn;
-        // hybrid batch: decode rows first, then this iteration's prefill rows; the first layer reads the two
-        // pieces where they are, later layers read the context's ping-pong buffers
-        char* cur = static_cast<char*>(ctx->xa);
-        char* nxt = static_cast<char*>(ctx->xb);
-        const RowSrc first{x_decode, D, static_cast<const char*>(x_prefill) + p0 * row_bytes};
-        for (int l = 0; l < n_layers; ++l) {
-            const RowSrc in = (l == 0) ? first : single_src(cur);
-            moe_status st;
-            if (l + 1 < n_layers) {
-                st = run_layer(ctx, layers[l], in, T, nxt, T, nxt, s);
-            } else {
-                void* yp = (P > 0) ? static_cast<char*>(y_prefill) + p0 * row_bytes : nullptr;
-                st = run_layer(ctx, layers[l], in, T, y_decode, D, yp, s);
+        // a decode-only call (no prompt rows) is one iteration whatever the group count
+        const int32_t G = (pn == 0) ? 1
+                          : (sched.n_groups > 0 ? sched.n_groups : moe_num_layer_groups(pn, n_layers, sched.granule));
+        st = moe_layer_groups(n_layers, G, first.data());
+        if (st != MOE_OK) return st;
+        const char* slice_in = static_cast<const char*>(x_prefill) + p0 * row_bytes;
+        char* slice_state = (P > 0) ? static_cast<char*>(y_prefill) + p0 * row_bytes : nullptr;
+        for (int32_t g = 0; g < G; ++g) {
+            for (int32_t j = 0; j < G; ++j) {
+                const moe_layer* gl = layers + first[j];
+                const int gn = first[j + 1] - first[j];
+                // the decode rows enter group 0 from x_decode and travel on in y_decode
+                const void* dec_in = (j == 0) ? x_decode : y_decode;
+                if (j == g && pn > 0) {
+                    const RowSrc in{dec_in, D, (g == 0) ? slice_in : slice_state};
+                    st = run_group(ctx, gl, gn, in, D + pn, y_decode, D, slice_state, s);
+                } else if (D > 0) {
+                    st = run_group(ctx, gl, gn, single_src(dec_in), D, y_decode, D, nullptr, s);
+                }
+                if (st != MOE_OK) return st;
             }
-            if (st != MOE_OK) return st;
-            char* t = cur; cur = nxt; nxt = t;
-            ctx->layer_passes += 1;
-            ctx->router_bytes += (uint64_t)g.E * g.H * ctx->esz;
+            ctx->iterations += 1;
+            ctx->tokens_processed += (uint64_t)(D + pn);
         }
-        ctx->iterations += 1;
-        ctx->tokens_processed += (uint64_t)T;
     }
     return MOE_OK;
 }

@@ -72,6 +72,29 @@ def test_create_rejects_bad_arguments_before_touching_the_gpu():
     assert lib.moe_router_topk(None, None, 4, None, None, None, None, None) == 1
 
 
+def test_group_count_rule_and_layer_groups_are_host_arithmetic():
+    # Sec. 4.4: N_lg(L) = max(1, ceil(L / 512)): 8192 tokens -> 16 groups, 512 tokens -> 1 group
+    assert binding.moe_num_layer_groups(8192, 48, 512) == 16
+    assert binding.moe_num_layer_groups(512, 48, 512) == 1
+    assert binding.moe_num_layer_groups(513, 48, 512) == 2
+    assert binding.moe_num_layer_groups(0, 48, 512) == 1
+    assert binding.moe_num_layer_groups(10 ** 9, 48, 512) == 48          # never more groups than layers
+    assert binding.moe_num_layer_groups(-1, 48, 512) == 0 and binding.moe_num_layer_groups(1, 0, 512) == 0
+    assert binding.moe_num_layer_groups(1, 48, 0) == 0
+    assert binding.moe_layer_groups(48, 16) == list(range(0, 49, 3))
+    assert binding.moe_layer_groups(10, 4) == [0, 3, 6, 8, 10]
+    lib = binding.load()
+    assert lib.moe_layer_groups(4, 2, None) == 1
+    buf = (ctypes.c_int32 * 8)()
+    assert lib.moe_layer_groups(4, 5, buf) == 2 and lib.moe_layer_groups(4, 0, buf) == 2
+
+
+def test_stack_forward_rejects_bad_arguments_before_touching_the_gpu():
+    lib = binding.load()
+    sched = binding.CStackSchedule(0, 1, 0)
+    assert lib.moe_stack_forward(None, None, 1, None, 0, None, 0, sched, None, None, None) == 1
+
+
 def test_binding_fails_loudly_without_the_library(monkeypatch):
     monkeypatch.setattr(binding, "_lib", None)
     monkeypatch.setattr(binding, "LIB_PATH", "/nonexistent/libmoe_lp.so")
