@@ -22,7 +22,8 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA
-BOUND = {"qwen3_layer": "hbm", "decode_large": "hbm", "qwen3_group8": None, "mixtral_zipf": "mfma", "tiny_f32": "hbm"}
+BOUND = {"qwen3_layer": "hbm", "decode_large": "hbm", "qwen3_group8": None, "mixtral_zipf": "mfma", "tiny_f32": "hbm",
+         "gptoss_layer": "hbm"}       # 264 rows per expert: below the ridge of ~312 flop/B
 
 
 def parse_args():
@@ -31,8 +32,17 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="qwen3_layer")
-    ap.add_argument("--schedule", default="layered", choices=["layered", "chunked"])
-    ap.add_argument("--chunk", type=int, default=0, help="chunk size for --schedule chunked (default: the workload's)")
+    ap.add_argument("--schedule", default="layered", choices=["layered", "chunked", "stack"],
+                    help="layered / chunked: the workload's layers as ONE layer group (moe_group_forward); "
+                         "stack: the workload's layers as a whole stack cut into --groups layer groups, one group "
+                         "per iteration carrying the prompt, with --chunk prompt tokens per outer pass "
+                         "(moe_stack_forward)")
+    ap.add_argument("--chunk", type=int, default=0,
+                    help="chunk size (chunked: default the workload's; stack: default 0 = the whole prompt)")
+    ap.add_argument("--groups", type=int, default=0,
+                    help="--schedule stack: number of layer groups (0 = max(1, ceil(slice / --granule)), at most layers)")
+    ap.add_argument("--granule", type=int, default=512, help="--schedule stack: tokens per iteration the group rule aims for")
+    ap.add_argument("--decode", type=int, default=-1, help="override the workload's number of decode tokens")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy kernel a few times (reference for scaling "
@@ -75,21 +85,31 @@ def main():
         print(json.dumps({"copy_calibration_bytes_read": n, "copy_calibration_bytes_written": n, "launches": 5}))
         return
     w = inputs.WORKLOADS[args.workload]
-    chunk = args.chunk or w.chunk
+    if args.decode >= 0:
+        w = inputs.scaled(w, D=args.decode)
+    stack = args.schedule == "stack"
+    chunk = args.chunk if stack else (args.chunk or w.chunk)
     dt = inputs.torch_dtype(w.dtype)
     esz = 2 if w.dtype == "bf16" else 4
 
     layers = [inputs.make_layer(w, l, device=dev) for l in range(w.n_layers)]
     xd, xp = inputs.make_hidden(w, device=dev)
-    T_iter = w.D + (w.P if args.schedule == "layered" else min(w.P, chunk))
+    if stack:
+        T_iter = w.D + (w.P if chunk == 0 else min(w.P, chunk))
+    else:
+        T_iter = w.D + (w.P if args.schedule == "layered" else min(w.P, chunk))
     ctx = binding.Context(w.H, w.E, w.K, w.I, dt, max_tokens=T_iter, residual=w.residual, device=dev)
     packed = ctx.pack_layers(layers)
     yd = torch.empty((w.D, w.H), dtype=dt, device=dev)
     yp = torch.empty((w.P, w.H), dtype=dt, device=dev)
 
     def step():
-        ctx.moe_group_forward(layers, xd if w.D else None, xp if w.P else None, args.schedule, chunk, packed=packed,
-                              y_decode=yd, y_prefill=yp)
+        if stack:
+            ctx.moe_stack_forward(layers, xd if w.D else None, xp if w.P else None, chunk=chunk, n_groups=args.groups,
+                                  granule=args.granule, packed=packed, y_decode=yd, y_prefill=yp)
+        else:
+            ctx.moe_group_forward(layers, xd if w.D else None, xp if w.P else None, args.schedule, chunk,
+                                  packed=packed, y_decode=yd, y_prefill=yp)
 
     for _ in range(args.warmup):
         step()
@@ -111,14 +131,20 @@ def main():
     value = tokens_per_step * args.steps / elapsed
 
     # ---- roofline of the dominant kernel (gate_up grouped GEMM), per launch ----
+    # (launches differ in size when decode-only passes mix with prompt passes: the figures are means over
+    # the launches; every layer sees the decode rows once per iteration and each prompt row once per step)
     launches_per_step = ctr.layer_passes / args.steps
     active_per_launch = ctr.active_experts_total / ctr.layer_passes
-    rows_per_launch = ctr.tokens_processed / ctr.iterations            # batch rows T of one iteration (average)
+    iters_per_step = ctr.iterations / args.steps
+    rows_per_launch = w.n_layers * (iters_per_step * w.D + w.P) / launches_per_step
     A = rows_per_launch * w.K
     alg_bytes = active_per_launch * 2 * w.I * w.H * esz + rows_per_launch * w.H * esz + A * w.I * esz
     alg_flops = 2.0 * A * w.H * 2 * w.I
     k_avg_s = k_ms / max(k_n, 1) * 1e-3
-    bound = BOUND.get(args.workload) or ("mfma" if args.schedule == "layered" else "hbm")
+    if stack:
+        bound = "mfma" if A / w.E > 312 else "hbm"      # mean rows per expert against the ridge (2.5 PFLOP/s / 8 TB/s)
+    else:
+        bound = BOUND.get(args.workload) or ("mfma" if args.schedule == "layered" else "hbm")
     variant = ctx.moe_ffn_variant(int(rows_per_launch))
     if bound == "hbm":
         achieved, peak, unit = alg_bytes / k_avg_s / 1e9, HBM_PEAK_GBS, "GB/s"
@@ -153,7 +179,8 @@ def main():
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": args.workload, "schedule": args.schedule,
-                   "chunk": chunk if args.schedule == "chunked" else None, "H": w.H, "E": w.E, "top_k": w.K,
+                   "chunk": chunk if args.schedule != "layered" else None,
+                   "groups": args.groups if stack else None, "granule": args.granule if stack else None, "H": w.H, "E": w.E, "top_k": w.K,
                    "I": w.I, "layers": w.n_layers, "decode_tokens": w.D, "prefill_tokens": w.P, "seed": w.seed},
         "roofline": roofline,
         "cpu_baseline": cpu,

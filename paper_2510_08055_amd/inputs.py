@@ -41,7 +41,7 @@ class Workload:
     residual: bool = True
 
 
-# The five benchmark workloads, in the order of the baseline description.
+# The five benchmark workloads, in the order of the baseline description, and a second model family.
 WORKLOADS = {
     "tiny_f32": Workload("tiny_f32", H=256, E=8, K=2, I=512, n_layers=1, D=0, P=64, dtype="f32",
                          chunk=16, seed=0, residual=False),
@@ -53,6 +53,10 @@ WORKLOADS = {
                              dtype="bf16", chunk=512, seed=3, zipf_s=1.2, residual=False),
     "decode_large": Workload("decode_large", H=2880, E=128, K=4, I=2880, n_layers=4, D=256, P=0,
                              dtype="bf16", chunk=512, seed=4),
+    # the second model family of Table 3 (32 experts, top-4, hidden size 2880; the intermediate size is not
+    # printed there: 2880 is the published GPT-OSS-20B value), one layer, 64 decode tokens + a 2048-token chunk
+    "gptoss_layer": Workload("gptoss_layer", H=2880, E=32, K=4, I=2880, n_layers=1, D=64, P=2048,
+                             dtype="bf16", chunk=512, seed=5, residual=False),
 }
 
 

@@ -108,3 +108,17 @@ def test_decode_large_group(gpu_lib):
     assert torch.equal(y_all, x)
     assert c.active_experts_total == active and c.expert_bytes == active * 3 * w.H * w.I * 2
     assert active >= 0.99 * w.n_layers * w.E        # 256 tokens x top-4 over 128 experts touch (nearly) all of them
+
+
+def test_gptoss_layer(gpu_lib):
+    # the second model family of Table 3: 32 experts, top-4, hidden size 2880 (264 rows per expert here)
+    w = inputs.WORKLOADS["gptoss_layer"]
+    L = inputs.make_layer(w, 0, device=DEV)
+    xd, xp = inputs.make_hidden(w, device=DEV)
+    T = w.D + w.P
+    ctx = gpu_lib.Context(w.H, w.E, w.K, w.I, torch.bfloat16, max_tokens=T, residual=w.residual, device=DEV)
+    yd, yp = ctx.moe_group_forward([L], xd, xp, "layered")
+    oc = check_layer(ctx, w, L, torch.cat([xd, xp]), torch.cat([yd, yp]), sample_rows(T, 12, 5), "gptoss_layer")
+    assert oc.sum() == T * w.K and oc.min() > 0
+    yd_c, yp_c = ctx.moe_group_forward([L], xd, xp, "chunked", w.chunk)
+    assert torch.equal(yd_c, yd) and torch.equal(yp_c, yp)
