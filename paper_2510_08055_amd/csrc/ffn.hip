@@ -319,7 +319,6 @@ __global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
     // in flight are the ones issued after activation stage g+1.
     constexpr int WAIT_MAIN = (NSMIN - 2) * LPS + (NSA < NSB ? B_LPW : NSB < NSA ? A_LPW : 0);
     constexpr int WAIT_FIRST = (NSA - 2) * A_LPW + (NSB - 2) * B_LPW;   // prologue loads after stage 0's
-    static_assert(NSMAX - NSMIN <= 1, "one ring is at most one stage deeper than the other");
     static_assert(WAIT_MAIN < 64 && WAIT_FIRST < 64, "vmcnt is a 6-bit counter");
 
     extern __shared__ __attribute__((aligned(1024))) char smem[];
@@ -360,9 +359,19 @@ __global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
     // Loads of one stage, cut into KS parts that are issued in the shadow of the MFMAs of the KS
     // k-slices of the stage being multiplied: load p of the step (activation loads first) goes with
     // slice p * KS / LPS.
+    // Lanes whose tile row lies past the tile's last row load nothing when that is safe: with NSA = 2 and
+    // the activation loads issued first, no wait count includes an activation load, so it does not matter
+    // whether a fully masked load instruction is issued or branched around.  The LDS rows they would have
+    // filled feed only accumulator rows that are never stored.
+    constexpr bool MASK_A = (NSA == 2 && ORD == 1);
+    bool a_live[A_LPW];
+#pragma unroll
+    for (int p = 0; p < A_LPW; ++p) a_live[p] = !MASK_A || ((wave + NW * p) * RPL + l_row) < rows_here;
     auto issue_a = [&](int kt, int p) {
-        __builtin_amdgcn_global_load_lds((glb_ptr_t*)(a_src[p] + kt * PBK),
-                                         (lds_ptr_t*)(smem + (kt % NSA) * A_SLOT + (wave + NW * p) * 1024), 16, 0, 0);
+        if (a_live[p])
+            __builtin_amdgcn_global_load_lds((glb_ptr_t*)(a_src[p] + kt * PBK),
+                                             (lds_ptr_t*)(smem + (kt % NSA) * A_SLOT + (wave + NW * p) * 1024), 16, 0,
+                                             0);
     };
     auto issue_b = [&](int kt, int p) {
         __builtin_amdgcn_global_load_lds((glb_ptr_t*)(b_src[p] + kt * PBK),

@@ -44,10 +44,12 @@ template <> struct vec8<float> {
 // added in wave order 0,1,2,3 through LDS, so the summation order of a logit is fixed by H alone.
 // Lane l supplies row (l % 16) of both operands; its quarter q = l / 16 owns the 8 consecutive
 // k-values [c*32 + q*8, c*32 + q*8 + 8) of chunk c and feeds them to 8 successive MFMAs (any fixed
-// pairing of k-slots is a valid summation order).  The raw operands of the next chunk are fetched
+// pairing of k-slots is a valid summation order).  The raw operands of the next chunks are fetched
 // while the MFMAs of the current one run; many short waves per SIMD hide the rest of the latency.
 // (32 x 32 tiles per block, each widened operand feeding two MFMAs, measured slower: a quarter as
 // many blocks leaves a 20 % tail on 256 compute units, and the matrix pipe, not the loads, is the limit.)
+constexpr int kRouterBufs = 4;
+
 template <typename T>
 __global__ __launch_bounds__(256) void router_logits_kernel(RowSrc x, int64_t n_tok, int H,
                                                             const T* __restrict__ wr,
@@ -71,7 +73,9 @@ __global__ __launch_bounds__(256) void router_logits_kernel(RowSrc x, int64_t n_
     const T* wp = wr + (int64_t)er * H + q * 8;
 
     double4_t acc = {0.0, 0.0, 0.0, 0.0};
-    vec8<T> xa[2], wa[2];
+    // ring of kRouterBufs operand buffers: the raw operands of the next kRouterBufs - 1 chunks of this wave
+    // are in flight while the MFMAs of the current chunk run (a wave's chunks are 128 k-values apart)
+    vec8<T> xa[kRouterBufs], wa[kRouterBufs];
     auto fetch = [&](int buf, int k0) {
         if (k0 + q * 8 < H) {
             xa[buf].load(xp + k0);
@@ -86,14 +90,19 @@ __global__ __launch_bounds__(256) void router_logits_kernel(RowSrc x, int64_t n_
         for (int j = 0; j < 8; ++j)
             acc = __builtin_amdgcn_mfma_f64_16x16x4f64(xa[buf].get(j), wa[buf].get(j), acc, 0, 0, 0);
     };
-    int k0 = wave * 32;
-    if (k0 < H) fetch(0, k0);
-    for (; k0 < H; k0 += 256) {
-        if (k0 + 128 < H) fetch(1, k0 + 128);
-        multiply(0);
-        if (k0 + 128 < H) {
-            if (k0 + 256 < H) fetch(0, k0 + 256);
-            multiply(1);
+    const int k_first = wave * 32;
+#pragma unroll
+    for (int b = 0; b < kRouterBufs - 1; ++b)
+        if (k_first + b * 128 < H) fetch(b, k_first + b * 128);
+    for (int k0 = k_first; k0 < H; k0 += kRouterBufs * 128) {
+#pragma unroll
+        for (int b = 0; b < kRouterBufs; ++b) {
+            const int kk = k0 + b * 128;
+            if (kk < H) {
+                const int ahead = kk + (kRouterBufs - 1) * 128;
+                if (ahead < H) fetch((b + kRouterBufs - 1) % kRouterBufs, ahead);
+                multiply(b);
+            }
         }
     }
     if (wave > 0) {
