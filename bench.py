@@ -43,6 +43,8 @@ def parse_args():
                     help="--schedule stack: number of layer groups (0 = max(1, ceil(slice / --granule)), at most layers)")
     ap.add_argument("--granule", type=int, default=512, help="--schedule stack: tokens per iteration the group rule aims for")
     ap.add_argument("--decode", type=int, default=-1, help="override the workload's number of decode tokens")
+    ap.add_argument("--route-skew", type=float, default=-1.0,
+                    help="override the workload's router popularity skew (std of a per-expert logit bias)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy kernel a few times (reference for scaling "
@@ -87,6 +89,8 @@ def main():
     w = inputs.WORKLOADS[args.workload]
     if args.decode >= 0:
         w = inputs.scaled(w, D=args.decode)
+    if args.route_skew >= 0:
+        w = inputs.scaled(w, route_skew=args.route_skew)
     stack = args.schedule == "stack"
     chunk = args.chunk if stack else (args.chunk or w.chunk)
     dt = inputs.torch_dtype(w.dtype)
@@ -181,7 +185,8 @@ def main():
         "config": {"workload": args.workload, "schedule": args.schedule,
                    "chunk": chunk if args.schedule != "layered" else None,
                    "groups": args.groups if stack else None, "granule": args.granule if stack else None, "H": w.H, "E": w.E, "top_k": w.K,
-                   "I": w.I, "layers": w.n_layers, "decode_tokens": w.D, "prefill_tokens": w.P, "seed": w.seed},
+                   "I": w.I, "layers": w.n_layers, "decode_tokens": w.D, "prefill_tokens": w.P, "seed": w.seed,
+                   "route_skew": w.route_skew},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "expert_bytes_per_step": ctr.expert_bytes // args.steps,

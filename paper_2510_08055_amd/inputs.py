@@ -39,6 +39,9 @@ class Workload:
     seed: int = 0
     zipf_s: float = 0.0   # > 0: router bias shaped so expert shares follow Zipf(s)
     residual: bool = True
+    route_skew: float = 0.0   # > 0: per-expert router bias ~ N(0, route_skew): some experts are popular, so a
+                              # decode batch covers fewer experts than under iid routing (Table 1 lies below
+                              # the iid curve 1 - (1 - k/E)^B for the same reason)
 
 
 # The five benchmark workloads, in the order of the baseline description, and a second model family.
@@ -102,6 +105,8 @@ def stored_router_bias(w: Workload, layer: int) -> Optional[torch.Tensor]:
     data/router_bias_<workload>.json (written by oracle/calibrate_zipf_bias.py).
     """
     if w.zipf_s <= 0:
+        if w.route_skew > 0:
+            return randn((w.E,), w.route_skew, w.seed, "route_skew_bias", layer, "f32", "cpu")
         return None
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "data", f"router_bias_{w.name}.json")
     with open(path) as f:
