@@ -103,7 +103,12 @@ __device__ __forceinline__ TileCoord find_tile(const int32_t* __restrict__ offse
     return tc;
 }
 
-__device__ __forceinline__ float silu_mul(float g, float u) { return g / (1.0f + __expf(-g)) * u; }
+// silu(g) * u with silu(g) = g / (1 + e^-g); hardware exp2 and reciprocal (1 ulp each), far inside the
+// rounding of the bf16 (or the tolerance of the fp32) result.
+__device__ __forceinline__ float silu_mul(float g, float u)
+{
+    return g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * u;
+}
 
 // ----------------------------------------------------------------------------------------------
 // LDS-tiled MFMA grouped GEMM.  256 threads = 4 waves arranged 2 (rows) x 2 (columns).
@@ -527,25 +532,52 @@ __global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
         }
         step(g, F{}, F{}, F{});
 
+        // Epilogue.  A lane holds, for output row fr of a row block, groups of 4 consecutive columns
+        // (accumulator element v of tile (i, j): column (v/4)*8 + fq*4 + v%4); storing them directly
+        // would scatter 8-byte pieces over 32 rows per instruction.  Each wave instead turns one row block
+        // at a time (32 rows x WNO columns, at most 4 KB) through a private piece of LDS and writes it
+        // out as whole 16-byte chunks, consecutive lanes along a row (64- or 128-byte runs per row).
+        // The LDS used is an activation slot no stage occupies any more: stage nk-1, the last one, sits
+        // in slot (nk-1) % NSA, and the readers of the other slots passed their barrier long ago, so no
+        // block barrier is needed; a wave's own LDS operations execute in program order.
+        constexpr int RB = TNO * 64;              // bytes of one row of the wave's output tile
+        constexpr int CPRW = TNO * 4;             // 16-byte chunks per such row
+        constexpr int REG = 32 * RB;              // bytes per wave
+        constexpr int WPS = A_SLOT / REG;         // waves per free activation slot
+        constexpr int RPI = 64 / CPRW;            // rows one wave-level 16-byte access covers
+        static_assert(TNO <= 2 && WPS >= 1 && (NSA - 1) * WPS >= NW, "the epilogue staging does not fit the free slots");
+        if (TMV > 0) {
+            char* epi = smem + ((nk_ + wave / WPS) % NSA) * A_SLOT + (wave % WPS) * REG;
+            auto eswz = [](int r) { return (r >> (RB == 64 ? 2 : 1)) & (CPRW - 1); };
 #pragma unroll
-        for (int i = 0; i < TMV; ++i) {
-            // accumulator element v of tile (i, j): output row fr of row block i, column (v/4)*8 + fq*4 + v%4
-            const int row = tc.row0 + (wm + WM * i) * 32 + fr;
+            for (int i = 0; i < TMV; ++i) {
 #pragma unroll
-            for (int j = 0; j < TNO; ++j) {
+                for (int j = 0; j < TNO; ++j) {
 #pragma unroll
-                for (int a = 0; a < 4; ++a) {
-                    const int col = n0 + wn * WNO + j * 32 + a * 8 + fq * 4;
-                    float val[4];
+                    for (int a = 0; a < 4; ++a) {
+                        float val[4];
 #pragma unroll
-                    for (int b = 0; b < 4; ++b) {
-                        if (GATED) val[b] = silu_mul(acc[i][j][a * 4 + b], acc[i][j + TNO][a * 4 + b]);
-                        else val[b] = acc[i][j][a * 4 + b];
-                    }
-                    if (row < tc.row_end && col < N)    // N is a multiple of 8: the 4 columns are in or out together
-                        *reinterpret_cast<uint2*>(Out + (int64_t)row * ldo + col) =
+                        for (int b = 0; b < 4; ++b) {
+                            if (GATED) val[b] = silu_mul(acc[i][j][a * 4 + b], acc[i][j + TNO][a * 4 + b]);
+                            else val[b] = acc[i][j][a * 4 + b];
+                        }
+                        const int chunk = (j * 4 + a) ^ eswz(fr);
+                        *reinterpret_cast<uint2*>(epi + fr * RB + chunk * 16 + fq * 8) =
                             make_uint2(pack_bf16x2(val[0], val[1]), pack_bf16x2(val[2], val[3]));
+                    }
                 }
+                __builtin_amdgcn_wave_barrier();
+                const int64_t row_base = (int64_t)tc.row0 + (wm + WM * i) * 32;
+#pragma unroll
+                for (int h = 0; h < 32 / RPI; ++h) {
+                    const int r = h * RPI + lane / CPRW, c = lane % CPRW;
+                    const uint4 v = *reinterpret_cast<const uint4*>(epi + r * RB + ((c ^ eswz(r)) * 16));
+                    const int64_t row = row_base + r;
+                    const int col = n0 + wn * WNO + c * 8;
+                    if (row < tc.row_end && col < N)    // N is a multiple of 8: a chunk is in or out as a whole
+                        *reinterpret_cast<uint4*>(Out + row * ldo + col) = v;
+                }
+                __builtin_amdgcn_wave_barrier();
             }
         }
     };
