@@ -40,7 +40,9 @@ struct TileCoord {
 // An expert with m rows is cut into ceil(m / BM) m-tiles of (nearly) equal size, each a whole number of
 // 32-row blocks: 1032 rows and BM = 256 give 224+224+224+192+168 rather than 4 x 256 + 8, so no block
 // streams a whole weight tile for a handful of rows.
-__device__ __forceinline__ TileCoord find_tile(const int32_t* __restrict__ offsets, int E, int BM, int n_tiles)
+// (The host bounds the grid so that the tile count fits 31 bits.)
+template <int BM>
+__device__ __forceinline__ TileCoord find_tile(const int32_t* __restrict__ offsets, int E, int n_tiles)
 {
     constexpr int EPL = kMaxExperts / 64;
     const int lane = lane_id();
@@ -63,43 +65,52 @@ __device__ __forceinline__ TileCoord find_tile(const int32_t* __restrict__ offse
         const int v = __shfl_up(incl, o, 64);
         if (lane >= o) incl += v;
     }
-    const int total_m = __shfl(incl, 63, 64);
-    const long total = (long)total_m * n_tiles;
-    const long chunk = (total + 7) / 8;
-    const long slot = blockIdx.x / 8;
-    const long logical = (long)(blockIdx.x % 8) * chunk + slot;
+    const int total = __shfl(incl, 63, 64) * n_tiles;
+    const int chunk = (total + 7) / 8;
+    const int slot = blockIdx.x / 8;
+    const int logical = (int)(blockIdx.x % 8) * chunk + slot;
     TileCoord tc;
     tc.valid = (slot < chunk) && (logical < total);
     tc.expert = 0; tc.row0 = 0; tc.row_end = 0; tc.n_tile = 0;
     if (!tc.valid) return tc;
-    // the lane whose experts contain the tile (tiles of an expert: mt_e * n_tiles, n-major)
-    const unsigned long long hit = __ballot(logical < (long)incl * n_tiles);
+    // the lane whose experts contain the tile (tiles of an expert: mt_e * n_tiles, n-major), then the
+    // expert among that lane's EPL; the one division happens after the choice
+    const unsigned long long hit = __ballot(logical < incl * n_tiles);
     const int src = __ffsll((long long)hit) - 1;
-    long rem = logical - (long)(incl - sum) * n_tiles;   // meaningful on lane src only
-    int expert = 0, row0 = 0, row_end = 0, n_tile = 0;
+    int rem = logical - (incl - sum) * n_tiles;   // meaningful on lane src only
+    int s_e = 0, s_lo = 0, s_hi = 0, s_mt = 1, s_rem = 0;
+    bool found = false;
 #pragma unroll
     for (int i = 0; i < EPL; ++i) {
-        const long cnt = (long)mt[i] * n_tiles;
-        if (rem >= 0 && rem < cnt) {
-            expert = lane * EPL + i;
-            n_tile = (int)(rem / mt[i]);
-            const int t = (int)(rem % mt[i]);
-            const int m = off[i + 1] - off[i];
-            const int rb = (m + 31) / 32;                       // 32-row blocks of this expert
-            const int per = (rb + mt[i] - 1) / mt[i];           // row blocks per tile
-            row0 = off[i] + t * per * 32;
-            row_end = row0 + per * 32;
-            if (row_end > off[i + 1]) row_end = off[i + 1];
-            if (row0 > row_end) row0 = row_end;                 // cannot happen: per * (mt - 1) < rb
-            rem = -1;
-        } else if (rem >= 0) {
-            rem -= cnt;
+        const int cnt = mt[i] * n_tiles;
+        const bool here = !found && rem < cnt;
+        if (here) {
+            s_e = lane * EPL + i;
+            s_lo = off[i];
+            s_hi = off[i + 1];
+            s_mt = mt[i];
+            s_rem = rem;
+            found = true;
         }
+        rem -= cnt;
     }
-    tc.expert = __shfl(expert, src, 64);
-    tc.row0 = __shfl(row0, src, 64);
-    tc.row_end = __shfl(row_end, src, 64);
-    tc.n_tile = __shfl(n_tile, src, 64);
+    s_e = __shfl(s_e, src, 64);
+    s_lo = __shfl(s_lo, src, 64);
+    s_hi = __shfl(s_hi, src, 64);
+    s_mt = __shfl(s_mt, src, 64);
+    s_rem = __shfl(s_rem, src, 64);
+    const int n_tile = s_rem / s_mt;
+    const int t = s_rem - n_tile * s_mt;
+    const int rb = (s_hi - s_lo + 31) / 32;                 // 32-row blocks of this expert
+    const int per = (rb + s_mt - 1) / s_mt;                 // row blocks per tile
+    int row0 = s_lo + t * per * 32;
+    int row_end = row0 + per * 32;
+    if (row_end > s_hi) row_end = s_hi;
+    if (row0 > row_end) row0 = row_end;                     // cannot happen: per * (mt - 1) < rb
+    tc.expert = s_e;
+    tc.row0 = row0;
+    tc.row_end = row_end;
+    tc.n_tile = n_tile;
     return tc;
 }
 
@@ -138,7 +149,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16_kernel(
     auto ldsB = [&](int buf) { return lds + buf * (A_ELEMS + B_ELEMS) + A_ELEMS; };
 
     const int n_tiles = (N + NO - 1) / NO;
-    const TileCoord tc = find_tile(offsets, E, BM, n_tiles);
+    const TileCoord tc = find_tile<BM>(offsets, E, n_tiles);
     if (!tc.valid) return;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -323,13 +334,13 @@ __global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
     // after them; loads return in issue order, so when stage g+1 is needed the loads that may still be
     // in flight are the ones issued after activation stage g+1.
     constexpr int WAIT_MAIN = (NSMIN - 2) * LPS + (NSA < NSB ? B_LPW : NSB < NSA ? A_LPW : 0);
-    constexpr int WAIT_FIRST = (NSA - 2) * A_LPW + (NSB - 2) * B_LPW;   // prologue loads after stage 0's
+    constexpr int WAIT_FIRST = (NSA - 2) * A_LPW;   // prologue: all weight stages, then the activation stages
     static_assert(WAIT_MAIN < 64 && WAIT_FIRST < 64, "vmcnt is a 6-bit counter");
 
     extern __shared__ __attribute__((aligned(1024))) char smem[];
 
     const int n_tiles = (N + NO - 1) / NO;
-    const TileCoord tc = find_tile(offsets, E, BM, n_tiles);
+    const TileCoord tc = find_tile<BM>(offsets, E, n_tiles);
     if (!tc.valid) return;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -340,17 +351,19 @@ __global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
     const int rb_valid = (rows_here + 31) / 32;   // row blocks of this tile with at least one real row
 
     // ---- source addresses of this lane's loads: group g = wave + NW*p covers tile rows RPL*g .. RPL*g + RPL-1 ----
+    // Order matters for the start-up latency: the row-map lookups are issued first, then (without waiting
+    // for them) the weight addresses are formed and the weight stages of the prologue are put in flight,
+    // and only then are the looked-up rows turned into activation addresses.
     const int l_row = lane / CPR, l_chunk = lane % CPR;
-    const bf16_t* a_src[A_LPW];
-    const bf16_t* b_src[B_LPW];
+    const int nk_ = K / PBK;
+    int32_t a_row_id[A_LPW];
 #pragma unroll
     for (int p = 0; p < A_LPW; ++p) {
-        const int tr = (wave + NW * p) * RPL + l_row;      // row inside the tile
-        int r = tc.row0 + tr;
+        int r = tc.row0 + (wave + NW * p) * RPL + l_row;
         if (r >= tc.row_end) r = tc.row_end - 1;
-        const int64_t src = row_map ? (int64_t)(row_map[r] / map_div) : (int64_t)r;
-        a_src[p] = row_ptr<bf16_t>(X, src, ldx) + ((l_chunk ^ swz<PBK>(tr)) << 3);
+        a_row_id[p] = row_map ? row_map[r] : r;
     }
+    const bf16_t* b_src[B_LPW];
 #pragma unroll
     for (int p = 0; p < B_LPW; ++p) {
         const int rb = (wave + NW * p) * RPL + l_row;
@@ -360,6 +373,23 @@ __global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
         if (n >= N) n = N - 1;
         if (GATED && rb >= NO) n += N;
         b_src[p] = We + (int64_t)n * K + ((l_chunk ^ swz<PBK>(rb)) << 3);
+    }
+    auto issue_b = [&](int kt, int p) {
+        __builtin_amdgcn_global_load_lds((glb_ptr_t*)(b_src[p] + kt * PBK),
+                                         (lds_ptr_t*)(smem + B_BASE + (kt % NSB) * B_SLOT + (wave + NW * p) * 1024), 16,
+                                         0, 0);
+    };
+#pragma unroll
+    for (int st = 0; st < NSB - 1; ++st)
+        if (st < nk_)
+#pragma unroll
+            for (int p = 0; p < B_LPW; ++p) issue_b(st, p);
+    const bf16_t* a_src[A_LPW];
+#pragma unroll
+    for (int p = 0; p < A_LPW; ++p) {
+        const int tr = (wave + NW * p) * RPL + l_row;      // row inside the tile
+        const int64_t src = row_map ? (int64_t)(a_row_id[p] / map_div) : (int64_t)a_row_id[p];
+        a_src[p] = row_ptr<bf16_t>(X, src, ldx) + ((l_chunk ^ swz<PBK>(tr)) << 3);
     }
     // Loads of one stage, cut into KS parts that are issued in the shadow of the MFMAs of the KS
     // k-slices of the stage being multiplied: load p of the step (activation loads first) goes with
@@ -377,11 +407,6 @@ __global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
             __builtin_amdgcn_global_load_lds((glb_ptr_t*)(a_src[p] + kt * PBK),
                                              (lds_ptr_t*)(smem + (kt % NSA) * A_SLOT + (wave + NW * p) * 1024), 16, 0,
                                              0);
-    };
-    auto issue_b = [&](int kt, int p) {
-        __builtin_amdgcn_global_load_lds((glb_ptr_t*)(b_src[p] + kt * PBK),
-                                         (lds_ptr_t*)(smem + B_BASE + (kt % NSB) * B_SLOT + (wave + NW * p) * 1024), 16,
-                                         0, 0);
     };
     // Load q of a step: ORD 0 alternates over the parts as A0 B0 | A1 B1 ..., ORD 1 issues the activation
     // loads first, ORD 2 the weight loads first.
@@ -415,7 +440,6 @@ __global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) k_off[kk] = ((kk * 2 + fq) ^ fsw) << 4;
 
-    const int nk_ = K / PBK;
     // Software pipeline.  Global side: activation stages g+1 .. g+NSA-1 and weight stages g+1 ..
     // g+NSB-1 are in flight while stage g is multiplied (the weight ring may be one stage deeper: the
     // weights are what comes from HBM).  LDS side: the operand fragments of k-slice kk+1 are read while
@@ -455,17 +479,14 @@ __global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[set][j], af[set][i], acc[i][j], 0, 0, 0);
         };
 
-        // prologue: stage 0 of both operands first, then the rest of what the rings hold
+        // prologue: the weight stages are already in flight; the activation stages follow, and the first
+        // wait lets through only the activation loads issued after stage 0's
 #pragma unroll
-        for (int st = 0; st < NSMAX - 1; ++st) {
-            if (st < NSA - 1 && st < nk_)
+        for (int st = 0; st < NSA - 1; ++st)
+            if (st < nk_)
 #pragma unroll
                 for (int p = 0; p < A_LPW; ++p) issue_a(st, p);
-            if (st < NSB - 1 && st < nk_)
-#pragma unroll
-                for (int p = 0; p < B_LPW; ++p) issue_b(st, p);
-        }
-        if (nk_ >= NSMAX - 1) wait_vmcnt<WAIT_FIRST>();
+        if (nk_ >= NSA - 1) wait_vmcnt<WAIT_FIRST>();
         else wait_vmcnt<0>();
         block_barrier();
         read_frags(0, 0, 0);
@@ -671,6 +692,7 @@ static hipError_t launch_tile(RowSrc X, int ldx, const int32_t* row_map, int map
     const int64_t n_tiles = (N + NO - 1) / NO;
     const int64_t m_tiles_max = (A + BM - 1) / BM + (A < E ? A : E);   // sum_e ceil(m_e / BM) never exceeds this
     const int64_t grid = ((m_tiles_max * n_tiles + 7) / 8) * 8;
+    if (grid >= ((int64_t)1 << 31)) return hipErrorInvalidValue;   // the device-side tile search counts in 32 bits
     kern<<<(unsigned)grid, 256, lds_bytes, s>>>(X, ldx, row_map, map_div, offsets, E, W, w_expert_stride, N, K, Out,
                                                 ldo);
     return hipGetLastError();
@@ -695,6 +717,7 @@ static hipError_t launch_pipe(RowSrc X, int ldx, const int32_t* row_map, int map
     const int64_t n_tiles = (N + NO - 1) / NO;
     const int64_t m_tiles_max = (A + BM - 1) / BM + (A < E ? A : E);
     const int64_t grid = ((m_tiles_max * n_tiles + 7) / 8) * 8;
+    if (grid >= ((int64_t)1 << 31)) return hipErrorInvalidValue;   // the device-side tile search counts in 32 bits
     kern<<<(unsigned)grid, NW * 64, lds_bytes, s>>>(X, ldx, row_map, map_div, offsets, E, W, w_expert_stride, N, K, Out,
                                                 ldo);
     return hipGetLastError();
