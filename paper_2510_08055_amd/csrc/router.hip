@@ -13,11 +13,22 @@ namespace moe {
 
 typedef double double4_t __attribute__((ext_vector_type(4)));
 
-template <typename T> struct vec8;  // 8 consecutive elements widened to double
+// 8 consecutive elements widened to double.  load_async() issues the global load as inline asm, so that
+// the compiler neither moves it nor waits for it: the caller waits with wait_loads<N>() (N = loads that may
+// still be in flight), which also names the registers as in/out operands, so no use of them can be
+// scheduled above the wait.
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+template <typename T> struct vec8;
 template <> struct vec8<bf16_t> {
-    uint4 raw;
-    __device__ __forceinline__ void load(const bf16_t* p) { raw = *reinterpret_cast<const uint4*>(p); }
-    __device__ __forceinline__ void zero() { raw = make_uint4(0, 0, 0, 0); }
+    static constexpr int kLoads = 1;
+    u32x4_t raw;
+    __device__ __forceinline__ void load(const bf16_t* p) { raw = *reinterpret_cast<const u32x4_t*>(p); }
+    __device__ __forceinline__ void load_async(const bf16_t* p)
+    {
+        asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(raw) : "v"(p) : "memory");
+    }
+    __device__ __forceinline__ void zero() { raw = u32x4_t{0, 0, 0, 0}; }
     __device__ __forceinline__ double get(int j) const
     {
         const uint32_t w = (j < 2) ? raw.x : (j < 4) ? raw.y : (j < 6) ? raw.z : raw.w;
@@ -25,19 +36,33 @@ template <> struct vec8<bf16_t> {
     }
 };
 template <> struct vec8<float> {
-    float4 a, b;
+    static constexpr int kLoads = 2;
+    f32x4_t a, b;
     __device__ __forceinline__ void load(const float* p)
     {
-        a = *reinterpret_cast<const float4*>(p);
-        b = *reinterpret_cast<const float4*>(p + 4);
+        a = *reinterpret_cast<const f32x4_t*>(p);
+        b = *reinterpret_cast<const f32x4_t*>(p + 4);
     }
-    __device__ __forceinline__ void zero() { a = b = make_float4(0.f, 0.f, 0.f, 0.f); }
+    __device__ __forceinline__ void load_async(const float* p)
+    {
+        asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(a) : "v"(p) : "memory");
+        asm volatile("global_load_dwordx4 %0, %1, off offset:16" : "=v"(b) : "v"(p) : "memory");
+    }
+    __device__ __forceinline__ void zero() { a = b = f32x4_t{0.f, 0.f, 0.f, 0.f}; }
     __device__ __forceinline__ double get(int j) const
     {
         const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
         return (double)v[j];
     }
 };
+template <int N> __device__ __forceinline__ void wait_loads(vec8<bf16_t>& x, vec8<bf16_t>& w)
+{
+    asm volatile("s_waitcnt vmcnt(%2)" : "+v"(x.raw), "+v"(w.raw) : "n"(N) : "memory");
+}
+template <int N> __device__ __forceinline__ void wait_loads(vec8<float>& x, vec8<float>& w)
+{
+    asm volatile("s_waitcnt vmcnt(%4)" : "+v"(x.a), "+v"(x.b), "+v"(w.a), "+v"(w.b) : "n"(N) : "memory");
+}
 
 // One block: a 16-token x 16-expert tile of logits with v_mfma_f64_16x16x4; its 4 waves split the
 // hidden dimension (wave w takes the 32-wide k-chunks w, w+4, w+8, ...) and their partial tiles are
@@ -73,37 +98,55 @@ __global__ __launch_bounds__(256) void router_logits_kernel(RowSrc x, int64_t n_
     const T* wp = wr + (int64_t)er * H + q * 8;
 
     double4_t acc = {0.0, 0.0, 0.0, 0.0};
-    // ring of kRouterBufs operand buffers: the raw operands of the next kRouterBufs - 1 chunks of this wave
-    // are in flight while the MFMAs of the current chunk run (a wave's chunks are 128 k-values apart)
+    // Ring of kRouterBufs operand buffers: the raw operands of this wave's next kRouterBufs - 1 chunks are
+    // in flight while the MFMAs of the current chunk run.  Loads and waits of the ring are explicit (the
+    // compiler would otherwise sink the loads next to their uses and wait for all of them); the look-ahead
+    // index is clamped to the wave's last whole chunk rather than tested, so the loop body is branch-free.
     vec8<T> xa[kRouterBufs], wa[kRouterBufs];
-    auto fetch = [&](int buf, int k0) {
-        if (k0 + q * 8 < H) {
-            xa[buf].load(xp + k0);
-            wa[buf].load(wp + k0);
-        } else {
-            xa[buf].zero();
-            wa[buf].zero();
-        }
-    };
     auto multiply = [&](int buf) {
 #pragma unroll
         for (int j = 0; j < 8; ++j)
             acc = __builtin_amdgcn_mfma_f64_16x16x4f64(xa[buf].get(j), wa[buf].get(j), acc, 0, 0, 0);
     };
-    const int k_first = wave * 32;
+    const int n_whole = H / 32;                                            // whole 32-wide chunks of a row
+    const int mine = n_whole > wave ? (n_whole - wave + 3) / 4 : 0;         // of which this wave takes chunks wave, wave+4, ...
+    auto fetch = [&](int buf, int i) {                                      // this wave's i-th chunk
+        const int k0 = (wave + 4 * i) * 32;
+        xa[buf].load_async(xp + k0);
+        wa[buf].load_async(wp + k0);
+    };
+    constexpr int kPerChunk = 2 * vec8<T>::kLoads;                          // load instructions per chunk
+    int i = 0;
+    if (mine >= kRouterBufs) {
 #pragma unroll
-    for (int b = 0; b < kRouterBufs - 1; ++b)
-        if (k_first + b * 128 < H) fetch(b, k_first + b * 128);
-    for (int k0 = k_first; k0 < H; k0 += kRouterBufs * 128) {
+        for (int b = 0; b < kRouterBufs - 1; ++b) fetch(b, b);
+        for (; i + kRouterBufs <= mine; i += kRouterBufs) {
 #pragma unroll
-        for (int b = 0; b < kRouterBufs; ++b) {
-            const int kk = k0 + b * 128;
-            if (kk < H) {
-                const int ahead = kk + (kRouterBufs - 1) * 128;
-                if (ahead < H) fetch((b + kRouterBufs - 1) % kRouterBufs, ahead);
+            for (int b = 0; b < kRouterBufs; ++b) {
+                const int ahead = i + b + kRouterBufs - 1;
+                fetch((b + kRouterBufs - 1) % kRouterBufs, ahead < mine ? ahead : mine - 1);
+                wait_loads<(kRouterBufs - 1) * kPerChunk>(xa[b], wa[b]);
                 multiply(b);
             }
         }
+        // the look-ahead loads of the last round are still in flight; they target ring registers
+        wait_loads<0>(xa[0], wa[0]);
+    }
+    for (; i < mine; ++i) {        // the last few whole chunks, one at a time
+        fetch(0, i);
+        wait_loads<0>(xa[0], wa[0]);
+        multiply(0);
+    }
+    if (H % 32 != 0 && wave == n_whole % 4) {      // the row's partial chunk: lanes past the end feed zeros
+        const int k0 = n_whole * 32;
+        if (k0 + q * 8 < H) {
+            xa[0].load(xp + k0);
+            wa[0].load(wp + k0);
+        } else {
+            xa[0].zero();
+            wa[0].zero();
+        }
+        multiply(0);
     }
     if (wave > 0) {
 #pragma unroll
