@@ -470,6 +470,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
                 bfr[set][j] = *reinterpret_cast<const bf16x8_t*>(base_b + b_row[j] + k_off[kk]);
         };
         auto mfma_set = [&](int set) {
+            __builtin_amdgcn_s_setprio(1);
 #pragma unroll
             for (int i = 0; i < TMV; ++i)
 #pragma unroll
@@ -477,6 +478,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
                     // weight rows as the MFMA's row operand, activation rows as its column operand: a lane then
                     // holds 4 consecutive OUTPUT COLUMNS of one output row, which the epilogue stores as 8 bytes
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[set][j], af[set][i], acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_s_setprio(0);
         };
 
         // prologue: the weight stages are already in flight; the activation stages follow, and the first
