@@ -18,7 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "liboracle.so")
 _lib = None
 
-F64, F32, BF16 = 0, 1, 2
+F64, F32, BF16, MXFP4 = 0, 1, 2, 3
 SCHED_CHUNKED, SCHED_LAYERED = 0, 1
 
 
@@ -129,27 +129,53 @@ def permute(idx, E):
     return counts, offsets, perm, inv
 
 
-def moe_layer(x, w_router, bias, w_gate_up, w_down, k, renormalize=True, residual=False, want_mag=False):
+def mxfp4_dequant(codes, scales):
+    """MXFP4 tensor -> float64: codes uint8 [..., n/2] (two FP4 E2M1 elements per byte, even element in the
+    low nibble), scales uint8 [..., n/32] (E8M0, one per 32 consecutive elements)."""
+    codes, scales = _c(codes, np.uint8), _c(scales, np.uint8)
+    n = codes.size * 2
+    assert scales.size * 32 == n
+    out = np.zeros(n, dtype=np.float64)
+    lib().orc_mxfp4_dequant(_p(codes), _p(scales), ctypes.c_int64(n), _p(out))
+    return out.reshape(codes.shape[:-1] + (codes.shape[-1] * 2,))
+
+
+def moe_layer(x, w_router, bias, w_gate_up, w_down, k, renormalize=True, residual=False, want_mag=False,
+              s_gate_up=None, s_down=None):
     """One MoE layer.  x [T,H]; w_router [E,H]; w_gate_up [E,2I,H]; w_down [E,H,I].
 
+    With s_gate_up / s_down given, the expert weights are MXFP4: w_gate_up uint8 [E,2I,H/2], s_gate_up
+    uint8 [E,2I,H/32], w_down uint8 [E,H,I/2], s_down uint8 [E,H,I/32]; the router stays as it is.
     Returns y [T,H] f64 (unrounded), idx [T,k] int32, w [T,k] f64 (and, with want_mag, y_mag [T,H] =
     sum_j w_j |expert output| (+ |x|): the magnitude of the terms y is summed from).
     """
-    x, w_router, w_gate_up, w_down = _c(x), _c(w_router), _c(w_gate_up), _c(w_down)
+    x, w_router = _c(x), _c(w_router)
     T, H = x.shape
     E = w_router.shape[0]
-    I = w_down.shape[2]
-    assert w_router.shape == (E, H) and w_gate_up.shape == (E, 2 * I, H) and w_down.shape == (E, H, I)
-    wdt = _dt(w_router)
-    assert _dt(w_gate_up) == wdt and _dt(w_down) == wdt
+    assert w_router.shape == (E, H)
+    rdt = _dt(w_router)
+    if s_gate_up is None:
+        w_gate_up, w_down = _c(w_gate_up), _c(w_down)
+        I = w_down.shape[2]
+        assert w_gate_up.shape == (E, 2 * I, H) and w_down.shape == (E, H, I)
+        wdt = rdt
+        assert _dt(w_gate_up) == wdt and _dt(w_down) == wdt
+        sgu = sd = None
+    else:
+        w_gate_up, w_down = _c(w_gate_up, np.uint8), _c(w_down, np.uint8)
+        sgu, sd = _c(s_gate_up, np.uint8), _c(s_down, np.uint8)
+        I = w_down.shape[2] * 2
+        assert w_gate_up.shape == (E, 2 * I, H // 2) and w_down.shape == (E, H, I // 2)
+        assert sgu.shape == (E, 2 * I, H // 32) and sd.shape == (E, H, I // 32)
+        wdt = MXFP4
     b = None if bias is None else _c(bias, np.float32)
     y = np.zeros((T, H), dtype=np.float64)
     idx = np.zeros((T, k), dtype=np.int32)
     w = np.zeros((T, k), dtype=np.float64)
     mag = np.zeros((T, H), dtype=np.float64) if want_mag else None
-    rc = lib().orc_moe_layer(_p(x), _dt(x), ctypes.c_int64(T), ctypes.c_int64(H), _p(w_router), _p(b),
-                             _p(w_gate_up), _p(w_down), wdt, E, k, ctypes.c_int64(I),
-                             int(bool(renormalize)), int(bool(residual)), _p(y), _p(idx), _p(w), _p(mag))
+    rc = lib().orc_moe_layer_q(_p(x), _dt(x), ctypes.c_int64(T), ctypes.c_int64(H), _p(w_router), rdt, _p(b),
+                               _p(w_gate_up), _p(sgu), _p(w_down), _p(sd), wdt, E, k, ctypes.c_int64(I),
+                               int(bool(renormalize)), int(bool(residual)), _p(y), _p(idx), _p(w), _p(mag))
     _check(rc, "moe_layer")
     if want_mag:
         return y, idx, w, mag

@@ -50,7 +50,7 @@
 #include <omp.h>
 #endif
 
-enum { ORC_F64 = 0, ORC_F32 = 1, ORC_BF16 = 2 };
+enum { ORC_F64 = 0, ORC_F32 = 1, ORC_BF16 = 2, ORC_MXFP4 = 3 /* expert weights only */ };
 enum { ORC_OK = 0, ORC_ERR_ARG = 1, ORC_ERR_NONFINITE = 2, ORC_ERR_ALLOC = 3 };
 enum { ORC_SCHED_CHUNKED = 0, ORC_SCHED_LAYERED = 1 };
 
@@ -213,21 +213,48 @@ int orc_permute(const int32_t *idx, int64_t T, int k, int E,
     return ORC_OK;
 }
 
+/*
+ * 4-bit expert weights (the paper's broader validation runs a model with fp4 expert weights, Table 7).
+ * The format is the published OCP Microscaling MXFP4: elements are FP4 E2M1 (1 sign, 2 exponent, 1
+ * mantissa bit: magnitudes 0, 0.5, 1, 1.5, 2, 3, 4, 6), two per byte with the even element in the low
+ * nibble; each run of 32 consecutive elements shares one E8M0 scale byte s, worth 2^(s - 127) (s = 255 is
+ * not a number and is rejected by the callers' finiteness check downstream).
+ * Element i of a tensor: code nibble i, scale byte i / 32 (rows are multiples of 32 long).
+ */
+double orc_mxfp4_element(const uint8_t *codes, const uint8_t *scales, int64_t i)
+{
+    static const double mag[8] = {0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0};
+    const unsigned c = (codes[i >> 1] >> ((i & 1) * 4)) & 15u;
+    const double v = (c & 8u) ? -mag[c & 7u] : mag[c & 7u];
+    return ldexp(v, (int)scales[i >> 5] - 127);
+}
+
+void orc_mxfp4_dequant(const uint8_t *codes, const uint8_t *scales, int64_t n, double *out)
+{
+    for (int64_t i = 0; i < n; ++i) out[i] = orc_mxfp4_element(codes, scales, i);
+}
+
+/* Expert-weight element i: plain formats through ld(), MXFP4 through its codes and scales. */
+static inline double ldw(const void *p, const uint8_t *scales, int dt, int64_t i)
+{
+    return dt == ORC_MXFP4 ? orc_mxfp4_element((const uint8_t *)p, scales, i) : ld(p, dt, i);
+}
+
 /* One expert FFN applied to one token (Sec. 2.1): o = Wd * (silu(Wg x) . Wu x). */
-static void expert_token(const double *xt, int64_t H, int64_t I, const void *Wgu, const void *Wd,
-                         int wdt, int e, double *a, double *o)
+static void expert_token(const double *xt, int64_t H, int64_t I, const void *Wgu, const uint8_t *Sgu,
+                         const void *Wd, const uint8_t *Sd, int wdt, int e, double *a, double *o)
 {
     const int64_t gu0 = (int64_t)e * 2 * I * H;
     for (int64_t i = 0; i < I; ++i) {
         double g = 0.0, u = 0.0;
-        for (int64_t h = 0; h < H; ++h) g += ld(Wgu, wdt, gu0 + i * H + h) * xt[h];
-        for (int64_t h = 0; h < H; ++h) u += ld(Wgu, wdt, gu0 + (I + i) * H + h) * xt[h];
+        for (int64_t h = 0; h < H; ++h) g += ldw(Wgu, Sgu, wdt, gu0 + i * H + h) * xt[h];
+        for (int64_t h = 0; h < H; ++h) u += ldw(Wgu, Sgu, wdt, gu0 + (I + i) * H + h) * xt[h];
         a[i] = g / (1.0 + exp(-g)) * u;
     }
     const int64_t d0 = (int64_t)e * H * I;
     for (int64_t h = 0; h < H; ++h) {
         double s = 0.0;
-        for (int64_t i = 0; i < I; ++i) s += ld(Wd, wdt, d0 + h * I + i) * a[i];
+        for (int64_t i = 0; i < I; ++i) s += ldw(Wd, Sd, wdt, d0 + h * I + i) * a[i];
         o[h] = s;
     }
 }
@@ -240,12 +267,39 @@ static void expert_token(const double *xt, int64_t H, int64_t I, const void *Wgu
  *   y_mag [T,H] (optional): sum_j w[t,j] * |expert output| (+ |x_t|), the magnitude of the terms y is
  *   made of; a caller uses it to size the rounding budget of a reduced-precision implementation.
  */
+int orc_moe_layer_q(const void *x, int xdt, int64_t T, int64_t H,
+                    const void *Wr, int rdt, const float *bias, const void *Wgu, const uint8_t *Sgu,
+                    const void *Wd, const uint8_t *Sd, int wdt,
+                    int E, int k, int64_t I, int renorm, int residual,
+                    double *y, int32_t *idx_out, double *w_out, double *y_mag);
+
 int orc_moe_layer(const void *x, int xdt, int64_t T, int64_t H,
                   const void *Wr, const float *bias, const void *Wgu, const void *Wd, int wdt,
                   int E, int k, int64_t I, int renorm, int residual,
                   double *y, int32_t *idx_out, double *w_out, double *y_mag)
 {
+    return orc_moe_layer_q(x, xdt, T, H, Wr, wdt, bias, Wgu, NULL, Wd, NULL, wdt, E, k, I, renorm, residual,
+                           y, idx_out, w_out, y_mag);
+}
+
+/*
+ * The same layer with the expert weights in their own format: wdt may be ORC_MXFP4, with Wgu / Wd the
+ * packed codes and Sgu / Sd the scale bytes (H and I multiples of 32); the router weights Wr stay in rdt.
+ */
+int orc_moe_layer_q(const void *x, int xdt, int64_t T, int64_t H,
+                    const void *Wr, int rdt, const float *bias, const void *Wgu, const uint8_t *Sgu,
+                    const void *Wd, const uint8_t *Sd, int wdt,
+                    int E, int k, int64_t I, int renorm, int residual,
+                    double *y, int32_t *idx_out, double *w_out, double *y_mag)
+{
     if (T < 0 || H <= 0 || I <= 0 || E <= 0 || k <= 0 || k > E) return ORC_ERR_ARG;
+    if (rdt == ORC_MXFP4) return ORC_ERR_ARG;
+    if (wdt == ORC_MXFP4 && (!Sgu || !Sd || H % 32 || I % 32)) return ORC_ERR_ARG;
+    if (wdt == ORC_MXFP4) {      /* scale byte 255 is the format's not-a-number */
+        const int64_t n_gu = (int64_t)E * 2 * I * H / 32, n_d = (int64_t)E * H * I / 32;
+        for (int64_t i = 0; i < n_gu; ++i) if (Sgu[i] == 255) return ORC_ERR_NONFINITE;
+        for (int64_t i = 0; i < n_d; ++i) if (Sd[i] == 255) return ORC_ERR_NONFINITE;
+    }
     int status = ORC_OK;
 #pragma omp parallel
     {
@@ -258,7 +312,7 @@ int orc_moe_layer(const void *x, int xdt, int64_t T, int64_t H,
 #pragma omp for schedule(dynamic, 1)
         for (int64_t t = 0; t < T; ++t) {
             for (int64_t h = 0; h < H; ++h) xt[h] = ld(x, xdt, t * H + h);
-            int rc = route_token(xt, H, Wr, wdt, bias, E, k, renorm, z, idx, w, NULL);
+            int rc = route_token(xt, H, Wr, rdt, bias, E, k, renorm, z, idx, w, NULL);
             if (rc != ORC_OK) {
 #pragma omp atomic write
                 status = rc;
@@ -269,7 +323,7 @@ int orc_moe_layer(const void *x, int xdt, int64_t T, int64_t H,
             for (int64_t h = 0; h < H; ++h) yt[h] = 0.0;
             if (mt) for (int64_t h = 0; h < H; ++h) mt[h] = 0.0;
             for (int j = 0; j < k; ++j) {
-                expert_token(xt, H, I, Wgu, Wd, wdt, idx[j], a, o);
+                expert_token(xt, H, I, Wgu, Sgu, Wd, Sd, wdt, idx[j], a, o);
                 for (int64_t h = 0; h < H; ++h) yt[h] += w[j] * o[h];
                 if (mt) for (int64_t h = 0; h < H; ++h) mt[h] += w[j] * fabs(o[h]);
             }
