@@ -23,7 +23,8 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA
 BOUND = {"qwen3_layer": "hbm", "decode_large": "hbm", "qwen3_group8": None, "mixtral_zipf": "mfma", "tiny_f32": "hbm",
-         "gptoss_layer": "hbm"}       # 264 rows per expert: below the ridge of ~312 flop/B
+         "gptoss_layer": "hbm",       # 264 rows per expert: below the ridge of ~312 flop/B
+         "decode_large_w4": "hbm"}
 
 
 def parse_args():
@@ -102,7 +103,9 @@ def main():
         T_iter = w.D + (w.P if chunk == 0 else min(w.P, chunk))
     else:
         T_iter = w.D + (w.P if args.schedule == "layered" else min(w.P, chunk))
-    ctx = binding.Context(w.H, w.E, w.K, w.I, dt, max_tokens=T_iter, residual=w.residual, device=dev)
+    ctx = binding.Context(w.H, w.E, w.K, w.I, dt, max_tokens=T_iter, residual=w.residual, device=dev,
+                          weight_format=w.weight_format)
+    wsz = 17.0 / 32.0 if w.weight_format == "mxfp4" else esz       # bytes per expert-weight element (codes + scales)
     packed = ctx.pack_layers(layers)
     yd = torch.empty((w.D, w.H), dtype=dt, device=dev)
     yp = torch.empty((w.P, w.H), dtype=dt, device=dev)
@@ -142,7 +145,7 @@ def main():
     iters_per_step = ctr.iterations / args.steps
     rows_per_launch = w.n_layers * (iters_per_step * w.D + w.P) / launches_per_step
     A = rows_per_launch * w.K
-    alg_bytes = active_per_launch * 2 * w.I * w.H * esz + rows_per_launch * w.H * esz + A * w.I * esz
+    alg_bytes = active_per_launch * 2 * w.I * w.H * wsz + rows_per_launch * w.H * esz + A * w.I * esz
     alg_flops = 2.0 * A * w.H * 2 * w.I
     k_avg_s = k_ms / max(k_n, 1) * 1e-3
     if stack:
@@ -170,7 +173,7 @@ def main():
         xn = inputs.to_numpy(x)
         t1 = time.perf_counter()
         oracle.moe_layer(xn, L0["w_router"], L0["router_bias"], L0["w_gate_up"], L0["w_down"], w.K,
-                         residual=w.residual)
+                         residual=w.residual, s_gate_up=L0.get("s_gate_up"), s_down=L0.get("s_down"))
         cpu_s = time.perf_counter() - t1
         # one layer over n_sample tokens; a step crosses n_layers layers per token
         cpu = {"value": round(n_sample / cpu_s / w.n_layers, 2), "unit": "tokens/s", "cores": oracle.num_threads(),
@@ -186,7 +189,7 @@ def main():
                    "chunk": chunk if args.schedule != "layered" else None,
                    "groups": args.groups if stack else None, "granule": args.granule if stack else None, "H": w.H, "E": w.E, "top_k": w.K,
                    "I": w.I, "layers": w.n_layers, "decode_tokens": w.D, "prefill_tokens": w.P, "seed": w.seed,
-                   "route_skew": w.route_skew},
+                   "route_skew": w.route_skew, "weight_format": w.weight_format or w.dtype},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "expert_bytes_per_step": ctr.expert_bytes // args.steps,

@@ -44,6 +44,15 @@ typedef enum {
 
 typedef enum { MOE_F32 = 0, MOE_BF16 = 1 } moe_dtype;
 
+/*
+ * Format of the expert weights (w_gate_up, w_down).  MOE_W_MXFP4 (the paper's broader validation, Table 7,
+ * runs a model with fp4 expert weights) is the published OCP Microscaling format: FP4 E2M1 elements
+ * (magnitudes 0, 0.5, 1, 1.5, 2, 3, 4, 6), two per byte with the even element in the low nibble, and one
+ * E8M0 scale byte (2^(s-127), s in 1..254) per 32 consecutive elements of a row.  It needs dtype ==
+ * MOE_BF16 (activations and the router stay bf16) and H, I multiples of 64.
+ */
+typedef enum { MOE_W_DTYPE = 0, MOE_W_MXFP4 = 1 } moe_weight_format;
+
 /* Shape of one MoE layer (Table 3 gives E, K and H of the evaluated models). */
 typedef struct {
     int32_t H;           /* hidden size, multiple of 8 */
@@ -53,6 +62,7 @@ typedef struct {
     int32_t dtype;       /* moe_dtype of activations and weights */
     int32_t renormalize; /* 1: mixing weights of the K selected experts are divided by their sum */
     int32_t residual;    /* 1: moe_group_forward links layers by x <- x + MoE(x); 0: x <- MoE(x) */
+    int32_t weight_format; /* moe_weight_format of the expert weights */
 } moe_config;
 
 /* Weights of one layer (device pointers). */
@@ -61,6 +71,9 @@ typedef struct {
     const float *router_bias; /* [E] fp32 added to the logits, or NULL */
     const void *w_gate_up;    /* [E, 2I, H] dtype; rows [0,I) gate projection, rows [I,2I) up projection */
     const void *w_down;       /* [E, H, I]  dtype */
+    /* MOE_W_MXFP4 only (else ignored): w_gate_up is [E, 2I, H/2] bytes, w_down [E, H, I/2] bytes, and */
+    const uint8_t *s_gate_up; /* [E, 2I, H/32] scale bytes */
+    const uint8_t *s_down;    /* [E, H, I/32]  scale bytes */
 } moe_layer;
 
 typedef enum { MOE_SCHED_CHUNKED = 0, MOE_SCHED_LAYERED = 1 } moe_sched_kind;
@@ -72,7 +85,8 @@ typedef struct {
 /* Expert-weight traffic model, accumulated by moe_group_forward (Sec. 5.4: a load
  * byte is counted whenever an expert's parameters are brought in for execution). */
 typedef struct {
-    uint64_t expert_bytes;         /* sum over (iteration, layer) of active experts * 3*H*I*sizeof(dtype) */
+    uint64_t expert_bytes;         /* sum over (iteration, layer) of active experts * bytes of one expert's weights:
+                                      3*H*I*sizeof(dtype), or 3*H*I*17/32 for MOE_W_MXFP4 (codes + scales) */
     uint64_t router_bytes;         /* sum over (iteration, layer) of E*H*sizeof(dtype) */
     uint64_t active_experts_total; /* sum over (iteration, layer) of experts with >= 1 token */
     uint64_t tokens_processed;     /* sum over iterations of the batch rows of that iteration */
@@ -126,6 +140,17 @@ moe_status moe_permute(moe_ctx *ctx, const void *x, const int32_t *topk_idx, int
  */
 moe_status moe_grouped_ffn(moe_ctx *ctx, const void *x_perm, const int32_t *offsets, int64_t A,
                            const void *w_gate_up, const void *w_down, void *y_perm, void *stream);
+
+/*
+ * The same step for a context created with weight_format == MOE_W_MXFP4 (Table 7: fp4 expert weights):
+ * w_gate_up / w_down are the packed codes, s_gate_up / s_down their scale bytes, layouts as in moe_layer.
+ * Every weight is widened exactly to bf16 on the fly; arithmetic and outputs as moe_grouped_ffn.
+ * MOE_ERR_DTYPE when the context's weight format is not MOE_W_MXFP4 (and moe_grouped_ffn returns it
+ * when it is).
+ */
+moe_status moe_grouped_ffn_mxfp4(moe_ctx *ctx, const void *x_perm, const int32_t *offsets, int64_t A,
+                                 const uint8_t *w_gate_up, const uint8_t *s_gate_up, const uint8_t *w_down,
+                                 const uint8_t *s_down, void *y_perm, void *stream);
 
 /*
  * Weighted un-permute and combine (Sec. 2.4: a token's output mixes its selected experts):

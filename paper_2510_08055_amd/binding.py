@@ -17,9 +17,11 @@ _lib = None
 
 MOE_F32, MOE_BF16 = 0, 1
 MOE_SCHED_CHUNKED, MOE_SCHED_LAYERED = 0, 1
+MOE_W_DTYPE, MOE_W_MXFP4 = 0, 1
+WEIGHT_FORMATS = {"": MOE_W_DTYPE, "dtype": MOE_W_DTYPE, "mxfp4": MOE_W_MXFP4}
 
 EXPORTS = ["moe_workspace_bytes", "moe_create", "moe_destroy", "moe_router_topk", "moe_permute",
-           "moe_grouped_ffn", "moe_combine", "moe_group_forward", "moe_num_layer_groups", "moe_layer_groups",
+           "moe_grouped_ffn", "moe_grouped_ffn_mxfp4", "moe_combine", "moe_group_forward", "moe_num_layer_groups", "moe_layer_groups",
            "moe_stack_forward", "moe_read_counters", "moe_reset_counters",
            "moe_kernel_timing", "moe_read_kernel_timing", "moe_ffn_variant", "moe_status_string"]
 
@@ -34,12 +36,14 @@ class MoeError(RuntimeError):
 
 class CConfig(ctypes.Structure):
     _fields_ = [("H", ctypes.c_int32), ("E", ctypes.c_int32), ("K", ctypes.c_int32), ("I", ctypes.c_int32),
-                ("dtype", ctypes.c_int32), ("renormalize", ctypes.c_int32), ("residual", ctypes.c_int32)]
+                ("dtype", ctypes.c_int32), ("renormalize", ctypes.c_int32), ("residual", ctypes.c_int32),
+                ("weight_format", ctypes.c_int32)]
 
 
 class CLayer(ctypes.Structure):
     _fields_ = [("w_router", ctypes.c_void_p), ("router_bias", ctypes.c_void_p),
-                ("w_gate_up", ctypes.c_void_p), ("w_down", ctypes.c_void_p)]
+                ("w_gate_up", ctypes.c_void_p), ("w_down", ctypes.c_void_p),
+                ("s_gate_up", ctypes.c_void_p), ("s_down", ctypes.c_void_p)]
 
 
 class CSchedule(ctypes.Structure):
@@ -82,6 +86,7 @@ def load():
     L.moe_router_topk.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp]
     L.moe_permute.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp, vp, vp]
     L.moe_grouped_ffn.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp]
+    L.moe_grouped_ffn_mxfp4.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp, vp, vp]
     L.moe_combine.argtypes = [vp, vp, vp, vp, vp, i64, vp, vp]
     L.moe_group_forward.argtypes = [vp, ctypes.POINTER(CLayer), i32, vp, i64, vp, i64, CSchedule, vp, vp, vp]
     L.moe_num_layer_groups.argtypes = [i64, i32, i32]
@@ -144,8 +149,8 @@ def _dtype_code(dt: torch.dtype) -> int:
     raise TypeError(f"unsupported dtype {dt}")
 
 
-def workspace_bytes(H, E, K, I, dtype, max_tokens, renormalize=True, residual=True) -> int:
-    cfg = CConfig(H, E, K, I, _dtype_code(dtype), int(renormalize), int(residual))
+def workspace_bytes(H, E, K, I, dtype, max_tokens, renormalize=True, residual=True, weight_format="") -> int:
+    cfg = CConfig(H, E, K, I, _dtype_code(dtype), int(renormalize), int(residual), WEIGHT_FORMATS[weight_format])
     out = ctypes.c_size_t(0)
     _check(load().moe_workspace_bytes(ctypes.byref(cfg), max_tokens, ctypes.byref(out)), "moe_workspace_bytes")
     return out.value
@@ -155,13 +160,15 @@ class Context:
     """A moe_ctx plus the torch-allocated workspace it lives on."""
 
     def __init__(self, H, E, K, I, dtype=torch.bfloat16, max_tokens=1024, renormalize=True, residual=True,
-                 device="cuda:0"):
+                 device="cuda:0", weight_format=""):
         self.lib = load()
         self.H, self.E, self.K, self.I = H, E, K, I
         self.dtype = dtype
         self.max_tokens = max_tokens
         self.device = torch.device(device)
-        self.cfg = CConfig(H, E, K, I, _dtype_code(dtype), int(renormalize), int(residual))
+        self.weight_format = weight_format
+        self.cfg = CConfig(H, E, K, I, _dtype_code(dtype), int(renormalize), int(residual),
+                           WEIGHT_FORMATS[weight_format])
         n = ctypes.c_size_t(0)
         _check(self.lib.moe_workspace_bytes(ctypes.byref(self.cfg), max_tokens, ctypes.byref(n)),
                "moe_workspace_bytes")
@@ -212,6 +219,14 @@ class Context:
                                         _ptr(y_perm), _stream()), "moe_grouped_ffn")
         return y_perm
 
+    def moe_grouped_ffn_mxfp4(self, x_perm, offsets, w_gate_up, s_gate_up, w_down, s_down):
+        A = x_perm.shape[0]
+        y_perm = torch.empty((A, self.H), dtype=self.dtype, device=self.device)
+        _check(self.lib.moe_grouped_ffn_mxfp4(self._ctx, _ptr(x_perm), _ptr(offsets), A, _ptr(w_gate_up),
+                                              _ptr(s_gate_up), _ptr(w_down), _ptr(s_down), _ptr(y_perm), _stream()),
+               "moe_grouped_ffn_mxfp4")
+        return y_perm
+
     def moe_combine(self, y_perm, inv_perm, topk_w, residual=None, out=None):
         T = topk_w.shape[0]
         y = out if out is not None else torch.empty((T, self.H), dtype=self.dtype, device=self.device)
@@ -224,8 +239,10 @@ class Context:
         arr = (CLayer * len(layers))()
         for i, L in enumerate(layers):
             b = L.get("router_bias")
+            sg, sd = L.get("s_gate_up"), L.get("s_down")
             arr[i] = CLayer(L["w_router"].data_ptr(), b.data_ptr() if b is not None else None,
-                            L["w_gate_up"].data_ptr(), L["w_down"].data_ptr())
+                            L["w_gate_up"].data_ptr(), L["w_down"].data_ptr(),
+                            sg.data_ptr() if sg is not None else None, sd.data_ptr() if sd is not None else None)
         return arr
 
     def moe_group_forward(self, layers, x_decode, x_prefill, schedule="layered", chunk=0, packed=None,

@@ -12,7 +12,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmoe_lp.so")
-SOURCES = ["api.hip", "router.hip", "permute.hip", "ffn.hip", "combine.hip"]
+SOURCES = ["api.hip", "router.hip", "permute.hip", "ffn.hip", "ffn_w4.hip", "combine.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]

@@ -39,6 +39,11 @@ moe_status check_cfg(const moe_config* c)
     if (c->H <= 0 || c->I <= 0 || c->E <= 0 || c->E > kMaxExperts || c->K <= 0 || c->K > c->E || c->K > kMaxTopK)
         return MOE_ERR_SHAPE;
     if (c->H % 8 || c->I % 8) return MOE_ERR_ALIGN;
+    if (c->weight_format != MOE_W_DTYPE && c->weight_format != MOE_W_MXFP4) return MOE_ERR_DTYPE;
+    if (c->weight_format == MOE_W_MXFP4) {
+        if (c->dtype != MOE_BF16) return MOE_ERR_DTYPE;
+        if (c->H % 64 || c->I % 64) return MOE_ERR_ALIGN;
+    }
     return MOE_OK;
 }
 
@@ -128,14 +133,23 @@ moe_status run_layer(moe_ctx* c, const moe_layer& L, RowSrc x, int64_t T, void* 
     }
     if (e != hipSuccess) return MOE_ERR_DEVICE;
     // the activation rows are gathered inside the gate_up GEMM's tile loads: no x_perm round trip
+    const bool w4 = g.weight_format == MOE_W_MXFP4;
     {
         Timed t(c, MOE_KERNEL_GATE_UP, s);
-        e = launch_ffn_gate_up(g.dtype, x, c->perm, g.K, c->offsets, A, g.E, g.H, g.I, L.w_gate_up, c->act, s);
+        if (w4)
+            e = launch_ffn_gate_up_w4(x, c->perm, g.K, c->offsets, A, g.E, g.H, g.I, (const uint8_t*)L.w_gate_up,
+                                      L.s_gate_up, c->act, s);
+        else
+            e = launch_ffn_gate_up(g.dtype, x, c->perm, g.K, c->offsets, A, g.E, g.H, g.I, L.w_gate_up, c->act, s);
     }
     if (e != hipSuccess) return MOE_ERR_DEVICE;
     {
         Timed t(c, MOE_KERNEL_DOWN, s);
-        e = launch_ffn_down(g.dtype, c->act, c->offsets, A, g.E, g.H, g.I, L.w_down, c->y_perm, s);
+        if (w4)
+            e = launch_ffn_down_w4(c->act, c->offsets, A, g.E, g.H, g.I, (const uint8_t*)L.w_down, L.s_down, c->y_perm,
+                                   s);
+        else
+            e = launch_ffn_down(g.dtype, c->act, c->offsets, A, g.E, g.H, g.I, L.w_down, c->y_perm, s);
     }
     if (e != hipSuccess) return MOE_ERR_DEVICE;
     {
@@ -180,6 +194,7 @@ moe_status check_stack_args(const moe_ctx* ctx, const moe_layer* layers, int32_t
         if (!layers[l].w_router || !layers[l].w_gate_up || !layers[l].w_down) return MOE_ERR_NULL;
         if (misaligned(layers[l].w_router) || misaligned(layers[l].w_gate_up) || misaligned(layers[l].w_down))
             return MOE_ERR_ALIGN;
+        if (ctx->cfg.weight_format == MOE_W_MXFP4 && (!layers[l].s_gate_up || !layers[l].s_down)) return MOE_ERR_NULL;
     }
     return MOE_OK;
 }
@@ -291,11 +306,30 @@ moe_status moe_grouped_ffn(moe_ctx* ctx, const void* x_perm, const int32_t* offs
     if (!x_perm || !offsets || !w_gate_up || !w_down || !y_perm) return MOE_ERR_NULL;
     if (misaligned(x_perm) || misaligned(w_gate_up) || misaligned(w_down) || misaligned(y_perm)) return MOE_ERR_ALIGN;
     const moe_config& g = ctx->cfg;
+    if (g.weight_format != MOE_W_DTYPE) return MOE_ERR_DTYPE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e = launch_ffn_gate_up(g.dtype, single_src(x_perm), nullptr, 1, offsets, A, g.E, g.H, g.I, w_gate_up,
                                       ctx->act, s);
     if (e != hipSuccess) return MOE_ERR_DEVICE;
     return dev(launch_ffn_down(g.dtype, ctx->act, offsets, A, g.E, g.H, g.I, w_down, y_perm, s));
+}
+
+moe_status moe_grouped_ffn_mxfp4(moe_ctx* ctx, const void* x_perm, const int32_t* offsets, int64_t A,
+                                 const uint8_t* w_gate_up, const uint8_t* s_gate_up, const uint8_t* w_down,
+                                 const uint8_t* s_down, void* y_perm, void* stream)
+{
+    if (!ctx) return MOE_ERR_NULL;
+    if (A < 0 || A > ctx->max_tokens * ctx->cfg.K) return MOE_ERR_SHAPE;
+    if (ctx->cfg.weight_format != MOE_W_MXFP4) return MOE_ERR_DTYPE;
+    if (A == 0) return MOE_OK;
+    if (!x_perm || !offsets || !w_gate_up || !s_gate_up || !w_down || !s_down || !y_perm) return MOE_ERR_NULL;
+    if (misaligned(x_perm) || misaligned(w_gate_up) || misaligned(w_down) || misaligned(y_perm)) return MOE_ERR_ALIGN;
+    const moe_config& g = ctx->cfg;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = launch_ffn_gate_up_w4(single_src(x_perm), nullptr, 1, offsets, A, g.E, g.H, g.I, w_gate_up, s_gate_up,
+                                         ctx->act, s);
+    if (e != hipSuccess) return MOE_ERR_DEVICE;
+    return dev(launch_ffn_down_w4(ctx->act, offsets, A, g.E, g.H, g.I, w_down, s_down, y_perm, s));
 }
 
 moe_status moe_combine(moe_ctx* ctx, const void* y_perm, const int32_t* inv_perm, const float* topk_w,
@@ -408,7 +442,9 @@ moe_status moe_read_counters(moe_ctx* ctx, moe_counters* out, void* stream)
     if (hipStreamSynchronize(s) != hipSuccess) return MOE_ERR_DEVICE;
     const moe_config& g = ctx->cfg;
     out->active_experts_total = active;
-    out->expert_bytes = (uint64_t)active * 3ull * (uint64_t)g.H * (uint64_t)g.I * (uint64_t)ctx->esz;
+    const uint64_t hi3 = 3ull * (uint64_t)g.H * (uint64_t)g.I;
+    // one expert's weights: dtype elements, or 4-bit codes plus one scale byte per 32 of them
+    out->expert_bytes = (uint64_t)active * (g.weight_format == MOE_W_MXFP4 ? hi3 / 2 + hi3 / 32 : hi3 * (uint64_t)ctx->esz);
     out->router_bytes = ctx->router_bytes;
     out->tokens_processed = ctx->tokens_processed;
     out->iterations = ctx->iterations;
@@ -453,6 +489,7 @@ const char* moe_ffn_variant(const moe_ctx* ctx, int64_t T)
 {
     if (!ctx) return "";
     const moe_config& g = ctx->cfg;
+    if (g.weight_format == MOE_W_MXFP4) return "grouped_gemm_w4_kernel<gated>";
     return ffn_variant_name(g.dtype, T * g.K, g.E, g.H, g.I);
 }
 

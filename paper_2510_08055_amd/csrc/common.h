@@ -85,4 +85,11 @@ hipError_t launch_ffn_down(int dtype, const void* act, const int32_t* offsets, i
                            const void* w_down, void* y_perm, hipStream_t s);
 const char* ffn_variant_name(int dtype, int64_t A, int E, int H, int I);
 
+// ffn_w4.hip: the same two GEMMs with MXFP4 expert weights (codes + scale bytes), bf16 activations
+hipError_t launch_ffn_gate_up_w4(RowSrc x, const int32_t* row_map, int map_div, const int32_t* offsets, int64_t A, int E,
+                                 int H, int I, const uint8_t* w_gate_up, const uint8_t* s_gate_up, void* act,
+                                 hipStream_t s);
+hipError_t launch_ffn_down_w4(const void* act, const int32_t* offsets, int64_t A, int E, int H, int I,
+                              const uint8_t* w_down, const uint8_t* s_down, void* y_perm, hipStream_t s);
+
 }  // namespace moe

@@ -8,118 +8,12 @@
 #include <stdlib.h>
 #include <string.h>
 
-#include <type_traits>
-
-#include "common.h"
+#include "ffn_tile.h"
 
 namespace moe {
 
-typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
-typedef float float16_t __attribute__((ext_vector_type(16)));
-
 constexpr int kBK = 64;        // k-extent of one LDS stage
 constexpr int kLdsStride = 72; // bf16 elements per LDS row: 64 + 8 pad -> 144 B, conflict-free 16 B reads
-
-// ----------------------------------------------------------------------------------------------
-// Work decomposition.  The launch grid is data-independent (an upper bound on the number of
-// tiles); every block finds its own (expert, m-tile, n-tile) from the device-side offsets and
-// blocks beyond the real tile count exit.  Experts without rows get no tile, so none of their
-// weights is read.
-//
-// Hardware hands consecutive workgroup ids to the 8 XCDs round-robin.  Logical tile ids are
-// therefore remapped so that each XCD walks one contiguous eighth of the logical order, and the
-// logical order is expert-major, then n-tile, then m-tile: the m-tiles that share one weight
-// tile run back to back on the same XCD (second and later reads hit that XCD's L2), and one
-// expert's activation rows stay in the same L2 while its n-tiles stream by.
-// ----------------------------------------------------------------------------------------------
-struct TileCoord {
-    int expert, row0, row_end, n_tile;   // rows [row0, row_end) of the permuted batch belong to this tile
-    bool valid;
-};
-
-// An expert with m rows is cut into ceil(m / BM) m-tiles of (nearly) equal size, each a whole number of
-// 32-row blocks: 1032 rows and BM = 256 give 224+224+224+192+168 rather than 4 x 256 + 8, so no block
-// streams a whole weight tile for a handful of rows.
-// (The host bounds the grid so that the tile count fits 31 bits.)
-template <int BM>
-__device__ __forceinline__ TileCoord find_tile(const int32_t* __restrict__ offsets, int E, int n_tiles)
-{
-    constexpr int EPL = kMaxExperts / 64;
-    const int lane = lane_id();
-    int off[EPL + 1];
-#pragma unroll
-    for (int i = 0; i <= EPL; ++i) {
-        const int e = lane * EPL + i;
-        off[i] = offsets[e <= E ? e : E];
-    }
-    int mt[EPL];
-    int sum = 0;
-#pragma unroll
-    for (int i = 0; i < EPL; ++i) {
-        mt[i] = (off[i + 1] - off[i] + BM - 1) / BM;
-        sum += mt[i];
-    }
-    int incl = sum;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        const int v = __shfl_up(incl, o, 64);
-        if (lane >= o) incl += v;
-    }
-    const int total = __shfl(incl, 63, 64) * n_tiles;
-    const int chunk = (total + 7) / 8;
-    const int slot = blockIdx.x / 8;
-    const int logical = (int)(blockIdx.x % 8) * chunk + slot;
-    TileCoord tc;
-    tc.valid = (slot < chunk) && (logical < total);
-    tc.expert = 0; tc.row0 = 0; tc.row_end = 0; tc.n_tile = 0;
-    if (!tc.valid) return tc;
-    // the lane whose experts contain the tile (tiles of an expert: mt_e * n_tiles, n-major), then the
-    // expert among that lane's EPL; the one division happens after the choice
-    const unsigned long long hit = __ballot(logical < incl * n_tiles);
-    const int src = __ffsll((long long)hit) - 1;
-    int rem = logical - (incl - sum) * n_tiles;   // meaningful on lane src only
-    int s_e = 0, s_lo = 0, s_hi = 0, s_mt = 1, s_rem = 0;
-    bool found = false;
-#pragma unroll
-    for (int i = 0; i < EPL; ++i) {
-        const int cnt = mt[i] * n_tiles;
-        const bool here = !found && rem < cnt;
-        if (here) {
-            s_e = lane * EPL + i;
-            s_lo = off[i];
-            s_hi = off[i + 1];
-            s_mt = mt[i];
-            s_rem = rem;
-            found = true;
-        }
-        rem -= cnt;
-    }
-    s_e = __shfl(s_e, src, 64);
-    s_lo = __shfl(s_lo, src, 64);
-    s_hi = __shfl(s_hi, src, 64);
-    s_mt = __shfl(s_mt, src, 64);
-    s_rem = __shfl(s_rem, src, 64);
-    const int n_tile = s_rem / s_mt;
-    const int t = s_rem - n_tile * s_mt;
-    const int rb = (s_hi - s_lo + 31) / 32;                 // 32-row blocks of this expert
-    const int per = (rb + s_mt - 1) / s_mt;                 // row blocks per tile
-    int row0 = s_lo + t * per * 32;
-    int row_end = row0 + per * 32;
-    if (row_end > s_hi) row_end = s_hi;
-    if (row0 > row_end) row0 = row_end;                     // cannot happen: per * (mt - 1) < rb
-    tc.expert = s_e;
-    tc.row0 = row0;
-    tc.row_end = row_end;
-    tc.n_tile = n_tile;
-    return tc;
-}
-
-// silu(g) * u with silu(g) = g / (1 + e^-g); hardware exp2 and reciprocal (1 ulp each), far inside the
-// rounding of the bf16 (or the tolerance of the fp32) result.
-__device__ __forceinline__ float silu_mul(float g, float u)
-{
-    return g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * u;
-}
 
 // ----------------------------------------------------------------------------------------------
 // LDS-tiled MFMA grouped GEMM.  256 threads = 4 waves arranged 2 (rows) x 2 (columns).
@@ -282,29 +176,6 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16_kernel(
 // The k-order of the MFMAs is the same as in the other variants (bit-identical results).
 // Requires K % PBK == 0.
 // ----------------------------------------------------------------------------------------------
-typedef __attribute__((address_space(3))) void lds_ptr_t;
-typedef __attribute__((address_space(1))) const void glb_ptr_t;
-
-// Waits and barriers of the software pipeline are inline asm with a memory clobber: the compiler must
-// not move LDS reads or the direct-to-LDS loads across them (the bare s_barrier intrinsic is not a
-// memory barrier for the optimiser, and __syncthreads() would drain every load still in flight).
-template <int N> __device__ __forceinline__ void wait_vmcnt()
-{
-    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-__device__ __forceinline__ void wait_lds_reads() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
-__device__ __forceinline__ void block_barrier() { asm volatile("s_barrier" ::: "memory"); }
-
-// Source-side swizzle of a tile row: which LDS 16-byte chunk slot holds global chunk c of row r is
-// c ^ swz(r).  Chosen so that the 16-byte operand reads of 8 (and of 16) consecutive rows fall into
-// distinct bank groups whether the LDS serves 128 or 256 bytes per clock.
-template <int PBK> __device__ __forceinline__ int swz(int r)
-{
-    if (PBK == 64) return (r & 7) ^ ((r >> 3) & 1);
-    return ((r >> 1) & 3) ^ ((r >> 3) & 1);
-}
-
 template <int RBM, int BN, int WM, int NSA, int NSB, int PBK, int MINW, int NW, int ORD, bool GATED>
 __global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
     RowSrc X, int ldx, const int32_t* __restrict__ row_map, int map_div,

@@ -39,6 +39,7 @@ class Workload:
     seed: int = 0
     zipf_s: float = 0.0   # > 0: router bias shaped so expert shares follow Zipf(s)
     residual: bool = True
+    weight_format: str = ""   # "" = expert weights in `dtype`; "mxfp4" = 4-bit codes + scale bytes (Table 7)
     route_skew: float = 0.0   # > 0: per-expert router bias ~ N(0, route_skew): some experts are popular, so a
                               # decode batch covers fewer experts than under iid routing (Table 1 lies below
                               # the iid curve 1 - (1 - k/E)^B for the same reason)
@@ -60,6 +61,10 @@ WORKLOADS = {
     # printed there: 2880 is the published GPT-OSS-20B value), one layer, 64 decode tokens + a 2048-token chunk
     "gptoss_layer": Workload("gptoss_layer", H=2880, E=32, K=4, I=2880, n_layers=1, D=64, P=2048,
                              dtype="bf16", chunk=512, seed=5, residual=False),
+    # 4-bit expert weights (Table 7 runs a model with fp4 expert weights): the decode-heavy shape again, the
+    # expert weights in MXFP4, so a pass streams 17/64 of the bf16 bytes
+    "decode_large_w4": Workload("decode_large_w4", H=2880, E=128, K=4, I=2880, n_layers=4, D=256, P=0,
+                                dtype="bf16", chunk=512, seed=6, weight_format="mxfp4"),
 }
 
 
@@ -115,13 +120,43 @@ def stored_router_bias(w: Workload, layer: int) -> Optional[torch.Tensor]:
     return torch.tensor(rec["bias"][layer], dtype=torch.float32)
 
 
+def rand_bytes(shape, lo: int, hi: int, seed: int, name: str, layer: int = 0, device: str = "cpu") -> torch.Tensor:
+    """uint8 tensor, uniform over [lo, hi], from the stream of (seed, name, layer) on `device`."""
+    g = torch.Generator(device=device)
+    g.manual_seed(_stream_seed(seed, name, layer))
+    numel = int(np.prod(shape))
+    out = torch.empty(shape, dtype=torch.uint8, device=device)
+    flat = out.view(-1)
+    step = 1 << 28
+    for s in range(0, numel, step):
+        n = min(step, numel - s)
+        flat[s:s + n] = torch.randint(lo, hi + 1, (n,), generator=g, device=device, dtype=torch.uint8)
+    return out
+
+
 def make_layer(w: Workload, layer: int, device: str = "cpu", with_bias: bool = True):
     """Random weights of one MoE layer: dict of w_router [E,H], router_bias, w_gate_up [E,2I,H], w_down [E,H,I].
 
     The (small) router tensors are always drawn on the CPU, so that they are the same bits wherever the
     (large) expert weights are drawn; everything is returned on `device`.
+
+    weight_format "mxfp4": the expert weights are drawn directly in their storage format (no quantiser is
+    involved): code bytes uniform over 0..255, i.e. every FP4 E2M1 value equally likely (rms 2.93), and
+    scale bytes uniform over 119..121 (2^-8 .. 2^-6), which gives weights of rms ~0.025, the scale of the
+    N(0, 0.02) weights of the other workloads.  w_gate_up is uint8 [E,2I,H/2] with s_gate_up uint8
+    [E,2I,H/32]; w_down uint8 [E,H,I/2] with s_down uint8 [E,H,I/32].
     """
     bias = stored_router_bias(w, layer) if with_bias else None
+    if w.weight_format == "mxfp4":
+        assert w.dtype == "bf16" and w.H % 64 == 0 and w.I % 64 == 0
+        return {
+            "w_router": randn((w.E, w.H), 0.02, w.seed, "w_router", layer, w.dtype, "cpu").to(device),
+            "router_bias": None if bias is None else bias.to(device),
+            "w_gate_up": rand_bytes((w.E, 2 * w.I, w.H // 2), 0, 255, w.seed, "w_gate_up_codes", layer, device),
+            "s_gate_up": rand_bytes((w.E, 2 * w.I, w.H // 32), 119, 121, w.seed, "w_gate_up_scales", layer, device),
+            "w_down": rand_bytes((w.E, w.H, w.I // 2), 0, 255, w.seed, "w_down_codes", layer, device),
+            "s_down": rand_bytes((w.E, w.H, w.I // 32), 119, 121, w.seed, "w_down_scales", layer, device),
+        }
     return {
         "w_router": randn((w.E, w.H), 0.02, w.seed, "w_router", layer, w.dtype, "cpu").to(device),
         "router_bias": None if bias is None else bias.to(device),

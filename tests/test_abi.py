@@ -15,7 +15,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def _declared():
     text = open(os.path.join(ROOT, "include", "moe_lp.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(moe_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(moe_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_library_exports_every_declared_symbol():
@@ -31,9 +31,9 @@ def test_status_strings():
     assert len({binding.status_string(i) for i in range(8)}) == 8
 
 
-def _ws(H=256, E=8, K=2, I=512, dtype=1, T=64):
+def _ws(H=256, E=8, K=2, I=512, dtype=1, T=64, wfmt=0):
     lib = binding.load()
-    cfg = binding.CConfig(H, E, K, I, dtype, 1, 1)
+    cfg = binding.CConfig(H, E, K, I, dtype, 1, 1, wfmt)
     n = ctypes.c_size_t(0)
     return lib.moe_workspace_bytes(ctypes.byref(cfg), T, ctypes.byref(n)), n.value
 
@@ -52,6 +52,11 @@ def test_workspace_bytes_and_argument_errors():
     assert _ws(dtype=7)[0] == 3      # unknown dtype    -> MOE_ERR_DTYPE
     assert _ws(H=257)[0] == 4        # H % 8 != 0       -> MOE_ERR_ALIGN
     assert _ws(I=12)[0] == 4
+    # 4-bit expert weights: bf16 activations only, H and I multiples of 64, 0/1 the only formats
+    assert _ws(wfmt=1)[0] == 0
+    assert _ws(wfmt=1, dtype=0)[0] == 3
+    assert _ws(wfmt=1, H=96)[0] == 4 and _ws(wfmt=1, I=96)[0] == 4
+    assert _ws(wfmt=2)[0] == 3
     lib = binding.load()
     assert lib.moe_workspace_bytes(None, 64, ctypes.byref(ctypes.c_size_t(0))) == 1   # MOE_ERR_NULL
     cfg = binding.CConfig(256, 8, 2, 512, 1, 1, 1)

@@ -1,0 +1,128 @@
+"""GPU parity of the 4-bit expert-weight path (MXFP4 weights, bf16 activations) through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2510_08055_amd import inputs
+from parity import assert_close
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def dev_layer(layer):
+    return {k: (v.to(DEV) if v is not None else None) for k, v in layer.items()}
+
+
+def make_ctx(lib, w, max_tokens):
+    return lib.Context(w.H, w.E, w.K, w.I, torch.bfloat16, max_tokens=max_tokens, residual=w.residual, device=DEV,
+                       weight_format=w.weight_format)
+
+
+def oracle_layer(w, Ln, xn, residual, rows=None):
+    x = xn if rows is None else xn[rows]
+    return oracle.moe_layer(x, Ln["w_router"], Ln["router_bias"], Ln["w_gate_up"], Ln["w_down"], w.K,
+                            residual=residual, want_mag=True, s_gate_up=Ln["s_gate_up"], s_down=Ln["s_down"])
+
+
+SHAPES = [
+    inputs.Workload("w4_small", H=128, E=4, K=2, I=64, n_layers=1, D=5, P=60, dtype="bf16", seed=61, residual=False,
+                    weight_format="mxfp4"),
+    inputs.Workload("w4_ragged", H=192, E=16, K=4, I=320, n_layers=1, D=9, P=333, dtype="bf16", seed=62,
+                    residual=False, weight_format="mxfp4"),           # 5 and 3 k-stages, ragged n-tiles, 64+ rows per expert
+    inputs.Workload("w4_sparse", H=2880, E=32, K=4, I=2880 // 5 * 1 // 64 * 64, n_layers=1, D=7, P=0, dtype="bf16",
+                    seed=63, residual=False, weight_format="mxfp4"),  # 45 k-stages, most experts with 0-2 rows
+]
+
+
+@pytest.mark.parametrize("w", SHAPES, ids=[w.name for w in SHAPES])
+def test_single_layer_steps(gpu_lib, w):
+    L = inputs.make_layer(w, 0)
+    Ld, Ln = dev_layer(L), inputs.layer_to_numpy(L)
+    xd, xp = inputs.make_hidden(w)
+    x = torch.cat([xd, xp]).to(DEV)
+    xn = inputs.to_numpy(x)
+    T = w.D + w.P
+    ctx = make_ctx(gpu_lib, w, T)
+    o_y, o_idx, o_w, mag = oracle_layer(w, Ln, xn, False)
+    # the grouped FFN step alone, on the oracle's routing
+    idx, wt = ctx.moe_router_topk(x, Ld["w_router"])
+    assert (idx.cpu().numpy() == o_idx).all()
+    counts, offsets, perm, inv, x_perm = ctx.moe_permute(x, idx)
+    y_perm = ctx.moe_grouped_ffn_mxfp4(x_perm, offsets, Ld["w_gate_up"], Ld["s_gate_up"], Ld["w_down"], Ld["s_down"])
+    y = ctx.moe_combine(y_perm, inv, wt)
+    assert_close(y, o_y, "bf16", w.name + " steps", mag=np.abs(o_y) + mag)
+    # the bf16 entry point refuses a 4-bit context
+    with pytest.raises(gpu_lib.MoeError) as e:
+        ctx.moe_grouped_ffn(x_perm, offsets, Ld["w_gate_up"], Ld["w_down"])
+    assert e.value.status == 3
+    # the whole layer in one call, both schedules, bit-identical
+    ctx.moe_reset_counters()
+    yd, yp = ctx.moe_group_forward([Ld], x[:w.D] if w.D else None, x[w.D:] if w.P else None, "layered")
+    c = ctx.moe_read_counters()
+    full = torch.cat([t for t in (yd, yp) if t.shape[0]])
+    assert torch.equal(full, y)
+    active = len(set(o_idx.reshape(-1).tolist()))
+    assert c.active_experts_total == active
+    assert c.expert_bytes == active * (3 * w.H * w.I // 2 + 3 * w.H * w.I // 32)      # codes + scale bytes
+    if w.P:
+        yd2, yp2 = ctx.moe_group_forward([Ld], x[:w.D] if w.D else None, x[w.D:], "chunked", 50)
+        assert torch.equal(torch.cat([yd2, yp2]), y)
+
+
+def test_group_with_residual_teacher_forced(gpu_lib):
+    w = inputs.Workload("w4_group", H=256, E=8, K=2, I=192, n_layers=3, D=6, P=90, dtype="bf16", seed=64,
+                        weight_format="mxfp4")
+    layers = [inputs.make_layer(w, l) for l in range(w.n_layers)]
+    dl = [dev_layer(L) for L in layers]
+    nl = [inputs.layer_to_numpy(L) for L in layers]
+    xd, xp = inputs.make_hidden(w)
+    ctx = make_ctx(gpu_lib, w, w.D + w.P)
+    x = torch.cat([xd, xp]).to(DEV)
+    for l in range(w.n_layers):
+        yd, yp = ctx.moe_group_forward([dl[l]], x[:w.D], x[w.D:], "layered")
+        y = torch.cat([yd, yp])
+        o_y, o_idx, _, mag = oracle_layer(w, nl[l], inputs.to_numpy(x), True)
+        idx, _ = ctx.moe_router_topk(x, dl[l]["w_router"])
+        assert (idx.cpu().numpy() == o_idx).all()
+        assert_close(y, o_y, "bf16", f"w4 group layer {l}", mag=np.abs(o_y) + mag)
+        x = y
+    yd, yp = ctx.moe_group_forward(dl, xd.to(DEV), xp.to(DEV), "layered")
+    assert torch.equal(torch.cat([yd, yp]), x)
+    yd, yp = ctx.moe_stack_forward(dl, xd.to(DEV), xp.to(DEV), chunk=40, n_groups=3)
+    assert torch.equal(torch.cat([yd, yp]), x)
+    # a layer without scale bytes is rejected before anything is launched
+    broken = dict(dl[0]); broken["s_down"] = None
+    with pytest.raises(gpu_lib.MoeError) as e:
+        ctx.moe_group_forward([broken], xd.to(DEV), xp.to(DEV), "layered")
+    assert e.value.status == 1
+
+
+def test_config_errors(gpu_lib):
+    with pytest.raises(gpu_lib.MoeError) as e:       # 4-bit weights need bf16 activations
+        gpu_lib.Context(128, 4, 2, 64, torch.float32, max_tokens=8, device=DEV, weight_format="mxfp4")
+    assert e.value.status == 3
+    with pytest.raises(gpu_lib.MoeError) as e:       # and H, I multiples of 64
+        gpu_lib.Context(96, 4, 2, 64, torch.bfloat16, max_tokens=8, device=DEV, weight_format="mxfp4")
+    assert e.value.status == 4
+
+
+def test_decode_large_w4_full_size_sampled(gpu_lib):
+    w = inputs.WORKLOADS["decode_large_w4"]
+    xd, _ = inputs.make_hidden(w, device=DEV)
+    ctx = make_ctx(gpu_lib, w, w.D)
+    L = inputs.make_layer(w, 0, device=DEV)
+    Ln = inputs.layer_to_numpy(L)
+    ctx.moe_reset_counters()
+    y, _ = ctx.moe_group_forward([L], xd, None, "layered")
+    c = ctx.moe_read_counters()
+    xn = inputs.to_numpy(xd)
+    o_idx, _ = oracle.router_topk(xn, Ln["w_router"], None, w.K)
+    idx, _ = ctx.moe_router_topk(xd, L["w_router"])
+    assert (idx.cpu().numpy() == o_idx).all()
+    rows = np.array([0, 77, 255])
+    o_y, _, _, mag = oracle_layer(w, Ln, xn, w.residual, rows)
+    assert_close(y[torch.from_numpy(rows).to(DEV)], o_y, "bf16", "decode_large_w4", mag=np.abs(o_y) + mag)
+    active = len(set(o_idx.reshape(-1).tolist()))
+    assert c.active_experts_total == active and c.expert_bytes == active * 3 * w.H * w.I * 17 // 32
