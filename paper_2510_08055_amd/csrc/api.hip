@@ -489,7 +489,7 @@ const char* moe_ffn_variant(const moe_ctx* ctx, int64_t T)
 {
     if (!ctx) return "";
     const moe_config& g = ctx->cfg;
-    if (g.weight_format == MOE_W_MXFP4) return "grouped_gemm_w4_kernel<gated>";
+    if (g.weight_format == MOE_W_MXFP4) return ffn_w4_variant_name(T * g.K, g.E);
     return ffn_variant_name(g.dtype, T * g.K, g.E, g.H, g.I);
 }
 

@@ -91,5 +91,6 @@ hipError_t launch_ffn_gate_up_w4(RowSrc x, const int32_t* row_map, int map_div, 
                                  hipStream_t s);
 hipError_t launch_ffn_down_w4(const void* act, const int32_t* offsets, int64_t A, int E, int H, int I,
                               const uint8_t* w_down, const uint8_t* s_down, void* y_perm, hipStream_t s);
+const char* ffn_w4_variant_name(int64_t A, int E);
 
 }  // namespace moe

@@ -61,7 +61,7 @@ __device__ __forceinline__ TileCoord find_tile(const int32_t* __restrict__ offse
     const int slot = blockIdx.x / 8;
     const int logical = (int)(blockIdx.x % 8) * chunk + slot;
     TileCoord tc;
-    tc.valid = (slot < chunk) && (logical < total);
+    tc.valid = __builtin_amdgcn_readfirstlane((slot < chunk) && (logical < total)) != 0;   // uniform: no divergent join below
     tc.expert = 0; tc.row0 = 0; tc.row_end = 0; tc.n_tile = 0;
     if (!tc.valid) return tc;
     // the lane whose experts contain the tile (tiles of an expert: mt_e * n_tiles, n-major), then the
@@ -98,10 +98,12 @@ __device__ __forceinline__ TileCoord find_tile(const int32_t* __restrict__ offse
     int row_end = row0 + per * 32;
     if (row_end > s_hi) row_end = s_hi;
     if (row0 > row_end) row0 = row_end;                     // cannot happen: per * (mt - 1) < rb
-    tc.expert = s_e;
-    tc.row0 = row0;
-    tc.row_end = row_end;
-    tc.n_tile = n_tile;
+    // the same in every lane: handed out as scalars, so that what the kernels derive from them (base
+    // addresses, row counts, the bookkeeping of the load pipeline) stays in scalar registers
+    tc.expert = __builtin_amdgcn_readfirstlane(s_e);
+    tc.row0 = __builtin_amdgcn_readfirstlane(row0);
+    tc.row_end = __builtin_amdgcn_readfirstlane(row_end);
+    tc.n_tile = __builtin_amdgcn_readfirstlane(n_tile);
     return tc;
 }
 

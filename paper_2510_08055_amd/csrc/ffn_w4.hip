@@ -18,6 +18,9 @@
 // Within a 64-wide stage lane (row, q) feeds k-block q (32 values) to four successive MFMAs, 8 values
 // each; the activation fragments follow the same k assignment.  Any fixed assignment is a valid
 // summation order; this kernel is the only 4-bit variant, so every schedule sees the same one.
+#include <cstdlib>
+#include <cstring>
+
 #include "ffn_tile.h"
 
 namespace moe {
@@ -32,20 +35,31 @@ constexpr int kW4NSA = 2, kW4NSB = 3;     // activation stages; weight DOUBLE st
 
 // Loads that may still be in flight while the wave goes on: the pipeline keeps count of the load
 // instructions it has issued and of the last one each stage needs, so the wait is exact in the start-up
-// and drain steps as well.  s_waitcnt takes an immediate: the count is rounded down to an even number.
+// and drain steps as well.  s_waitcnt takes an immediate: the count is rounded down to the next value in the tree.
 __device__ __forceinline__ void wait_vmcnt_at_most(int n)
 {
-    if (n >= 20) wait_vmcnt<20>();
-    else if (n >= 18) wait_vmcnt<18>();
-    else if (n >= 16) wait_vmcnt<16>();
-    else if (n >= 14) wait_vmcnt<14>();
-    else if (n >= 12) wait_vmcnt<12>();
-    else if (n >= 10) wait_vmcnt<10>();
-    else if (n >= 8) wait_vmcnt<8>();
-    else if (n >= 6) wait_vmcnt<6>();
-    else if (n >= 4) wait_vmcnt<4>();
-    else if (n >= 2) wait_vmcnt<2>();
-    else wait_vmcnt<0>();
+    if (n >= 10) {
+        if (n >= 16) {
+            if (n >= 20) wait_vmcnt<20>();
+            else if (n >= 18) wait_vmcnt<18>();
+            else wait_vmcnt<16>();
+        } else {
+            if (n >= 14) wait_vmcnt<14>();
+            else if (n >= 12) wait_vmcnt<12>();
+            else wait_vmcnt<10>();
+        }
+    } else {
+        if (n >= 4) {
+            if (n >= 8) wait_vmcnt<8>();
+            else if (n >= 6) wait_vmcnt<6>();
+            else wait_vmcnt<4>();
+        } else {
+            if (n >= 3) wait_vmcnt<3>();
+            else if (n >= 2) wait_vmcnt<2>();
+            else if (n >= 1) wait_vmcnt<1>();
+            else wait_vmcnt<0>();
+        }
+    }
 }
 
 // 8 FP4 values (one dword) times the block's scale -> 8 bf16, in k order.
@@ -94,7 +108,8 @@ __global__ __launch_bounds__(kW4Waves * 64, 2) void grouped_gemm_w4_kernel(
     const TileCoord tc = find_tile<BM>(offsets, E, n_tiles);
     if (!tc.valid) return;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);    // wave-uniform: the load bookkeeping stays in scalar registers
     const int wn = wave;
     const int n0 = tc.n_tile * NO;
     const int nk = K / PBK;
@@ -323,26 +338,402 @@ __global__ __launch_bounds__(kW4Waves * 64, 2) void grouped_gemm_w4_kernel(
     }
 }
 
+// ----------------------------------------------------------------------------------------------
+// The weight-streaming shape for decode-heavy batches (on average at most 32 rows per expert).
+//
+// With 4-bit weights a 64-value stage is 32 bytes of a weight row: fetched stage by stage (or two
+// stages at a time) every 128-byte line of the weights is requested several times, a few stages
+// apart, and a row whose start is not line-aligned (1440-byte rows: every row but one in four)
+// straddles lines on top of that.  Measured on 128 experts x 5760 x 2880: 1.5x the weight bytes
+// cross the fabric and the kernel stays at 0.37 of the HBM peak.  Here every weight row is fetched
+// in whole, ALIGNED 128-byte lines: line L of a row holds the row's bytes [128 L - phase, 128 L -
+// phase + 128), phase = (row address) mod 128, a multiple of 32, so a stage's 32 bytes never cross a
+// line and stage s of a row of class c = phase / 32 lies in line (c + s) / 4 at 32-byte slot
+// (c + s) % 4.  A row keeps two lines in LDS; when it moves on to line L - 1 (top of stage
+// 4 (L - 1) - c) the line slot it has just left takes line L, four stages ahead of its first use.
+// Rows of different classes turn over at different stages, so in the common case (row bytes an odd
+// multiple of 32) a quarter of the rows fetches a line at every stage and the traffic is even.
+//
+// 32 x 256 tiles, 8 waves, each with its own 32 weight rows: a wave fetches the lines of its own
+// rows, so only the activation tile is shared between waves.  The per-stage work of a wave is small
+// (4 MFMAs behind 16 conversions) and the stage is a chain of dependent waits, so the kernel lives on
+// the number of waves per SIMD (4) and on the length of that chain: every instruction on it costs.
+// The load schedule is therefore fixed, with nothing to keep count of.  Every stage issues the same
+// loads: [the activations of stage g + 3,] then line ((c + g) / 4) + 1 of the rows whose class c has
+// (c + g) % 4 = 0; the start-up issues what stages -3, -2, -1 would have.  Past a row's end the rule
+// simply fetches the next line of memory (the next row's bytes, into the line slot the row has
+// left for good), past the last stage the activation load repeats the last stage into a free slot:
+// harmless, and the loads in flight at the top of a stage are always the same, so the wait count is
+// a constant (row bytes an odd multiple of 32: one line load per stage) or one of four (else).
+// Loads return in order, so the wait for the activations of stage g also covers every line issued
+// before them: the activation ring (4 stages) runs as far ahead as the lines do.  The scale bytes
+// never touch LDS: a lane needs one byte per stage for its weight row and holds them in registers
+// (128 bytes of the row at a time).  For the gated GEMM waves 0-3 hold the gate rows and waves 4-7
+// the matching up rows; the up accumulators cross through LDS once, after the last stage.  80 KB of
+// LDS, two blocks per compute unit.
+// ----------------------------------------------------------------------------------------------
+constexpr int kS4Rows = 32, kS4NSA = 4, kS4Waves = 8;
+
+// 16 bytes into registers without a compiler-inserted wait: the value may be used only after an explicit
+// wait that covers the load, followed by settle().
+__device__ __forceinline__ u32x4_t load_u32x4_async(const uint8_t* p)
+{
+    u32x4_t v;
+    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(v) : "v"(p) : "memory");
+    return v;
+}
+__device__ __forceinline__ void settle(u32x4_t& v) { asm volatile("" : "+v"(v)::"memory"); }
+
+// ODD: the row bytes are an odd multiple of 32 (the four line loads of a wave have the four classes).
+// (second launch bound: waves per SIMD; two blocks of 8 waves per compute unit = 4)
+template <bool GATED, bool ODD>
+__global__ __launch_bounds__(kS4Waves * 64, 4) void grouped_gemm_w4_stream_kernel(
+    RowSrc X, int ldx, const int32_t* __restrict__ row_map, int map_div, const int32_t* __restrict__ offsets, int E,
+    const uint8_t* __restrict__ W, const uint8_t* __restrict__ S, int64_t rows_per_expert, int N, int K,
+    bf16_t* __restrict__ Out, int ldo)
+{
+    constexpr int BM = kS4Rows, BN = kW4BN, NW = kS4Waves, NSA = kS4NSA, PBK = kW4K;
+    constexpr int NO = GATED ? BN / 2 : BN;     // output columns per block
+    constexpr int A_ROWB = PBK * 2, A_SLOT = BM * A_ROWB;        // 128-byte activation rows, 4 KB per stage
+    constexpr int B_SLOT = BN * 128;                             // one 128-byte line of every weight row
+    constexpr int B_BASE = NSA * A_SLOT;
+    constexpr int B_LPW = BN / 8 / NW;                           // line loads per wave to cover its rows once (8 rows each)
+    static_assert(BM == 32 && BN == 32 * NW && B_LPW == 4 && NSA == 4, "tile configuration");
+
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+
+    const int n_tiles = (N + NO - 1) / NO;
+    const TileCoord tc = find_tile<BM>(offsets, E, n_tiles);
+    if (!tc.valid) return;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);    // wave-uniform: what depends on it stays in scalar registers
+    const int n0 = tc.n_tile * NO;
+    const int nk = K / PBK;
+    const int64_t row_bytes = K / 2, row_scales = K / 32;
+    const uint8_t* We = W + (int64_t)tc.expert * rows_per_expert * row_bytes;
+    const uint8_t* Se = S + (int64_t)tc.expert * rows_per_expert * row_scales;
+    const uint8_t* W_last = W + (int64_t)E * rows_per_expert * row_bytes - 16;     // last 16 bytes of the codes
+    const uint8_t* S_end = S + (int64_t)E * rows_per_expert * row_scales;
+
+    // activations: waves 0..3 fetch tile rows wave * 8 .. + 7, lane = (row, 16-byte chunk)
+    const int a_lrow = lane >> 3, a_chunk = lane & 7;
+    const int tile_rows = tc.row_end - tc.row0;     // 1 .. 32
+    const bool a_loader = wave * 8 < tile_rows;     // (false for waves 4..7); a load whose rows all lie past the tile's last row is left out
+    int32_t a_row_id;
+    {
+        int r = tc.row0 + wave * 8 + a_lrow;
+        if (r >= tc.row_end) r = tc.row_end - 1;
+        a_row_id = r;
+        // fetched without a compiler-tracked wait: the weight loads below go out while it is in flight, and
+        // the explicit wait in front of its first use leaves exactly those outstanding
+        if (row_map) asm volatile("global_load_dword %0, %1, off" : "=v"(a_row_id) : "v"(row_map + r) : "memory");
+    }
+
+    // Tile row t -> row of the expert's weight matrix.  A row past the matrix (ragged last n-tile) is
+    // replaced by the last real row with the same index mod 4, which has the same line phase; what it
+    // produces is never stored.
+    auto weight_row = [&](int t) {
+        const bool up = GATED && t >= NO;
+        int n = n0 + (up ? t - NO : t);
+        if (n >= N) n -= ((n - N) / 4 + 1) * 4;
+        return up ? n + N : n;
+    };
+    // Line loads: load k of this wave covers its 8 rows 32 wave + 4 i + q_k, i = lane / 8: rows 4 apart start
+    // a multiple of 128 bytes apart, so they share a class.  When the row bytes are an odd multiple of 32
+    // the four residues q have four different classes and q_k is the residue of class k (load k has class
+    // k, known at compile time); otherwise q_k = k.  The instruction's 8 lines are LDS rows 8 (4 wave +
+    // k) .. + 7; LDS chunk x of a row holds the line's chunk x ^ sw(row), sw chosen so that 16 lanes
+    // reading the chunks of their stage (which differ between classes) fall into 16 different bank
+    // groups.
+    const int rb32 = (int)(row_bytes >> 5) & 3;
+    const int c0 = __builtin_amdgcn_readfirstlane(
+        (int)((uintptr_t)(We + (int64_t)weight_row(32 * wave) * row_bytes) >> 5) & 3);     // class of residue 0
+    auto line_sw = [&](int t) {
+        const int i = (t >> 2) & 7, q = t & 3;
+        const int xq = ODD ? 0 : (rb32 == 2 ? (q >> 1) : q);
+        return ((i >> 1) & 1) | (xq << 1);
+    };
+    const uint8_t* b_src[B_LPW];       // this lane's 16 bytes of line 0
+    int cls[B_LPW];                    // the load's class (wave-uniform; = k when ODD)
+    bool clamp_any = false;            // some address this wave will ask for lies outside W (wave-uniform)
+#pragma unroll
+    for (int k = 0; k < B_LPW; ++k) {
+        const int q = ODD ? ((k - c0) * rb32) & 3 : k;     // rb32 is its own inverse mod 4
+        const int t = 32 * wave + 4 * (lane >> 3) + q;
+        const uint8_t* row = We + (int64_t)weight_row(t) * row_bytes;
+        const int phase = (int)((uintptr_t)row & 127);
+        b_src[k] = row - phase + (((lane & 7) ^ line_sw(t)) << 4);
+        cls[k] = ODD ? k : __builtin_amdgcn_readfirstlane(phase >> 5);
+        // the first line may begin in front of W; the last line asked for is ((cls + nk - 1) / 4) + 1
+        const int l_last = ((cls[k] + nk - 1) >> 2) + 1;
+        clamp_any = clamp_any || __ballot(b_src[k] < W || b_src[k] + (int64_t)l_last * 128 > W_last) != 0;
+    }
+    // this lane's operand row: tile row 32 wave + fr, k-half fq of every stage
+    const int fr = lane & 31, fq = lane >> 5;
+    const int t_own = 32 * wave + fr;
+    const int wr_own = weight_row(t_own);
+    const int k_own = ODD ? (c0 + rb32 * (fr & 3)) & 3 : (fr & 3);     // the load that fetches this row
+    const int b_off = ((wave * 4 + k_own) * 8 + (fr >> 2)) * 128;
+    const int b_sw = line_sw(t_own);
+    const int b_cls = ODD ? k_own : (int)((uintptr_t)(We + (int64_t)wr_own * row_bytes) >> 5) & 3;
+    const uint8_t* s_src = Se + (int64_t)wr_own * row_scales;     // both k-halves of a row fetch the same scale bytes
+    // A row's scale bytes are fetched 128 at a time (64 stages; the whole row when K <= 4096) as up to 8
+    // 16-byte pieces: neighbouring rows then touch the lines they share at the same moment, whereas
+    // piecemeal fetches of 16 bytes every 8 stages brought each line in several times.  A lane keeps the 8
+    // bytes of a piece that belong to its k-half (byte u of them is the scale of stage 8 piece + u).
+    const int s_row_pieces = (int)((row_scales + 15) / 16);     // 16-byte pieces that hold bytes of the row
+    int s_over = 0;                    // bytes by which the row's LAST piece would pass the end of S: it is fetched that much earlier
+    {
+        const int over = (int)(s_src + (int64_t)s_row_pieces * 16 - S_end);
+        s_over = over > 0 ? over : 0;
+    }
+    uint32_t s_lo[8], s_hi[8], s_cur_lo = 0, s_cur_hi = 0;
+    auto fetch_piece = [&](int piece) {
+        return load_u32x4_async(s_src + piece * 16 - (piece == s_row_pieces - 1 ? s_over : 0));
+    };
+    auto keep_piece = [&](u32x4_t v, int piece, uint32_t& lo_out, uint32_t& hi_out) {
+        settle(v);
+        if (piece == s_row_pieces - 1 && s_over > 0) {      // the row's last piece started s_over bytes early
+            uint64_t lo = (uint64_t)v[0] | ((uint64_t)v[1] << 32);
+            uint64_t hi = (uint64_t)v[2] | ((uint64_t)v[3] << 32);
+            const int sh = s_over * 8;
+            if (sh >= 64) {
+                lo = hi >> (sh - 64);
+                hi = 0;
+            } else {
+                lo = (lo >> sh) | (hi << (64 - sh));
+                hi >>= sh;
+            }
+            v = u32x4_t{(uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32)};
+        }
+        const uint32_t sel = fq ? 0x07050301u : 0x06040200u;      // bytes fq, fq + 2, fq + 4, fq + 6 of a dword pair
+        lo_out = __builtin_amdgcn_perm(v[1], v[0], sel);
+        hi_out = __builtin_amdgcn_perm(v[3], v[2], sel);
+    };
+
+    // ---- the fixed load schedule ----
+    const bf16_t* a_src = nullptr;
+    // the loads of (pseudo-)stage g, g >= -3: activations of stage g + 3 into the slot stage g - 1 used, then
+    // the lines that come due
+    auto issue_stage = [&](int g, int a_slot) {
+        if (a_loader) {
+            const int kt = g + NSA - 1 < nk ? g + NSA - 1 : nk - 1;
+            if (wave * 8 + a_lrow < tile_rows)
+                __builtin_amdgcn_global_load_lds((glb_ptr_t*)(a_src + kt * PBK),
+                                                 (lds_ptr_t*)(smem + a_slot * A_SLOT + wave * 1024), 16, 0, 0);
+        }
+#pragma unroll
+        for (int k = 0; k < B_LPW; ++k) {
+            if (ODD ? ((k + g) & 3) != 0 : ((cls[k] + g) & 3) != 0) continue;
+            const int L = ((cls[k] + g) >> 2) + 1;
+            const uint8_t* a = b_src[k] + (int64_t)L * 128;
+            if (clamp_any) a = a > W_last ? W_last : a;      // (only the wave that holds the last rows of W)
+            __builtin_amdgcn_global_load_lds((glb_ptr_t*)a,
+                                             (lds_ptr_t*)(smem + B_BASE + (L & 1) * B_SLOT + (wave * B_LPW + k) * 1024),
+                                             16, 0, 0);
+        }
+    };
+    // Loads in flight at the top of stage g that stage g does not need: the lines of stages g-3, g-2, g-1
+    // and the activations of stages g-2, g-1.
+    int lines_at[4];                   // line loads of a stage = r (mod 4)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        lines_at[r] = 0;
+#pragma unroll
+        for (int k = 0; k < B_LPW; ++k) lines_at[r] += ((cls[k] + r) & 3) == 0;
+    }
+    auto wait_for_stage = [&](int r) {     // r = g mod 4, a compile-time constant where it is called
+        if (ODD) {
+            if (a_loader) wait_vmcnt<5>();
+            else wait_vmcnt<3>();
+        } else {
+            const int n = lines_at[(r + 1) & 3] + lines_at[(r + 2) & 3] + lines_at[(r + 3) & 3] + (a_loader ? 2 : 0);
+            wait_vmcnt_at_most(n);
+        }
+    };
+
+    // ---- start-up: scale bytes, line 0 of every row, then what stages -3, -2, -1 would issue ----
+    u32x4_t s_raw[8];                  // the first 8 pieces, until the row-map lookup below has returned
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+        if (i < s_row_pieces) s_raw[i] = fetch_piece(i);
+#pragma unroll
+    for (int k = 0; k < B_LPW; ++k) {
+        const uint8_t* a = b_src[k];
+        if (clamp_any) {
+            a = a < W ? W : a;
+            a = a > W_last ? W_last : a;
+        }
+        __builtin_amdgcn_global_load_lds((glb_ptr_t*)a, (lds_ptr_t*)(smem + B_BASE + (wave * B_LPW + k) * 1024), 16, 0, 0);
+    }
+    {
+        // the row-map load and the scale pieces came before the 4 line loads: wait for them, cut the pieces
+        // down to this lane's bytes
+        wait_vmcnt<B_LPW>();
+        asm volatile("" : "+v"(a_row_id)::"memory");
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            if (i < s_row_pieces) keep_piece(s_raw[i], i, s_lo[i], s_hi[i]);
+        const int tr = wave * 8 + a_lrow;
+        const int64_t src = row_map ? (int64_t)(a_row_id / map_div) : (int64_t)a_row_id;
+        a_src = row_ptr<bf16_t>(X, src, ldx) + ((a_chunk ^ swz<64>(tr)) << 3);
+    }
+    issue_stage(-3, 0);
+    issue_stage(-2, 1);
+    issue_stage(-1, 2);
+
+    const int fsw = swz<64>(fr);
+    const int a_off = fr * A_ROWB;
+    // token columns past the tile's rows are never stored: their lanes skip the activation reads (with a
+    // handful of rows per expert most of the LDS read traffic would be for nothing)
+    const bool a_reader = fr < ((tile_rows + 7) & ~7);
+
+    float16_t acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+    bf16x8_t af[4];
+#pragma unroll
+    for (int j4 = 0; j4 < 4; ++j4)
+#pragma unroll
+        for (int v = 0; v < 8; ++v) af[j4][v] = (__bf16)0.f;
+
+    for (int g0 = 0; g0 < nk; g0 += 8) {
+        const int chunk = g0 >> 3;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int g = g0 + u;
+            if (g >= nk) break;
+            wait_for_stage(u & 3);
+            block_barrier();       // every wave's part of stage g is in LDS; every wave is done reading stage g-1
+            if (u == 0) {          // the scale bytes of stages g0 .. g0 + 7: piece g0 / 8 of the row
+                if (chunk > 0 && (chunk & 7) == 0) {
+                    // K > 4096: the next 128 scale bytes, two pieces at a time, each pair awaited on the spot
+                    // (once per 64 stages; everything issued earlier lands as well, which the fixed wait
+                    // counts of the next stages allow for)
+#pragma unroll
+                    for (int i = 0; i < 8; i += 2) {
+                        if (chunk + i < s_row_pieces) {
+                            u32x4_t t0 = fetch_piece(chunk + i), t1 = t0;
+                            if (chunk + i + 1 < s_row_pieces) t1 = fetch_piece(chunk + i + 1);
+                            wait_vmcnt<0>();
+                            keep_piece(t0, chunk + i, s_lo[i], s_hi[i]);
+                            keep_piece(t1, chunk + i + 1, s_lo[i + 1], s_hi[i + 1]);
+                        }
+                    }
+                }
+                switch (chunk & 7) {
+                    case 0: s_cur_lo = s_lo[0]; s_cur_hi = s_hi[0]; break;
+                    case 1: s_cur_lo = s_lo[1]; s_cur_hi = s_hi[1]; break;
+                    case 2: s_cur_lo = s_lo[2]; s_cur_hi = s_hi[2]; break;
+                    case 3: s_cur_lo = s_lo[3]; s_cur_hi = s_hi[3]; break;
+                    case 4: s_cur_lo = s_lo[4]; s_cur_hi = s_hi[4]; break;
+                    case 5: s_cur_lo = s_lo[5]; s_cur_hi = s_hi[5]; break;
+                    case 6: s_cur_lo = s_lo[6]; s_cur_hi = s_hi[6]; break;
+                    default: s_cur_lo = s_lo[7]; s_cur_hi = s_hi[7]; break;
+                }
+            }
+            // the operand reads go out first, the loads of this stage are issued while they return
+            const char* a_base = smem + (u & 3) * A_SLOT + a_off;
+            if (a_reader) {
+#pragma unroll
+                for (int j4 = 0; j4 < 4; ++j4)
+                    af[j4] = *reinterpret_cast<const bf16x8_t*>(a_base + (((fq * 4 + j4) ^ fsw) << 4));
+            }
+            const int tt = b_cls + g;
+            const int y = ((tt & 3) << 1) | fq;
+            const u32x4_t bq = *reinterpret_cast<const u32x4_t*>(smem + B_BASE + ((tt >> 2) & 1) * B_SLOT + b_off +
+                                                                 ((y ^ b_sw) << 4));
+            issue_stage(g, (u + NSA - 1) & 3);
+            const float sc = e8m0_to_float((((u & 4) ? s_cur_hi : s_cur_lo) >> ((u & 3) * 8)) & 0xffu);
+#pragma unroll
+            for (int j4 = 0; j4 < 4; ++j4) {
+                // weight rows as the MFMA's row operand: a lane ends up with 4 consecutive output columns
+                const bf16x8_t wv = widen_fp4x8(bq[j4], sc);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv, af[j4], acc, 0, 0, 0);
+            }
+            wait_lds_reads();   // this wave's reads of stage g have returned before it reaches the next barrier
+        }
+    }
+    // The line and activation loads of the last stages are still in flight; nothing reads them, but the
+    // accumulator exchange below writes LDS, and a block must not end with loads into LDS outstanding.
+    wait_vmcnt<0>();
+
+    // accumulator element v: output row fr, column (v/4)*8 + fq*4 + v%4 of the wave's 32 columns
+    if (GATED) {
+        // The up waves hand their accumulators to the gate waves through their own weight rows in LDS (no
+        // other wave reads those, and every line fetched into them has been used): 4 KB per wave, quad a of
+        // lane l at a * 1024 + l * 16.
+        char* xch = smem + B_BASE + wave * 4 * 1024;
+        if (wave >= 4) {
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+                *reinterpret_cast<float4*>(xch + a * 1024 + lane * 16) =
+                    make_float4(acc[a * 4], acc[a * 4 + 1], acc[a * 4 + 2], acc[a * 4 + 3]);
+            wait_lds_reads();
+        }
+        block_barrier();
+        if (wave >= 4) return;
+    }
+    const int64_t row = (int64_t)tc.row0 + fr;
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+        const int col = n0 + (wave & (GATED ? 3 : 7)) * 32 + a * 8 + fq * 4;
+        float val[4];
+        if (GATED) {
+            const float4 up = *reinterpret_cast<const float4*>(smem + B_BASE + (wave + 4) * 4 * 1024 + a * 1024 + lane * 16);
+            val[0] = silu_mul(acc[a * 4 + 0], up.x);
+            val[1] = silu_mul(acc[a * 4 + 1], up.y);
+            val[2] = silu_mul(acc[a * 4 + 2], up.z);
+            val[3] = silu_mul(acc[a * 4 + 3], up.w);
+        } else {
+#pragma unroll
+            for (int b = 0; b < 4; ++b) val[b] = acc[a * 4 + b];
+        }
+        if (row < tc.row_end && col < N)    // N is a multiple of 8: the 4 columns are in or out together
+            *reinterpret_cast<uint2*>(Out + row * ldo + col) =
+                make_uint2(pack_bf16x2(val[0], val[1]), pack_bf16x2(val[2], val[3]));
+    }
+}
+
+// Which kernel shape a launch uses: the streaming shape when the experts hold at most 32 rows on average
+// (its 32-row tiles re-read and re-widen the weights once per 32 rows, which a prefill-heavy batch would
+// pay for), else the 64-row tiles.
+bool w4_use_stream(int64_t A, int E)
+{
+    const char* force = getenv("MOE_FFN_VARIANT");    // tuning and test aid: "w4_tile64", "w4_stream"
+    if (force && !strcmp(force, "w4_tile64")) return false;
+    if (force && !strcmp(force, "w4_stream")) return true;
+    return A <= (int64_t)32 * E;
+}
+
 template <bool GATED>
 hipError_t launch_w4(RowSrc X, int ldx, const int32_t* row_map, int map_div, const int32_t* offsets, int E, int64_t A,
                      const uint8_t* W, const uint8_t* S, int64_t rows_per_expert, int N, int K, bf16_t* Out, int ldo,
                      hipStream_t s)
 {
     constexpr int NO = GATED ? kW4BN / 2 : kW4BN;
-    const size_t lds_bytes = (size_t)kW4NSA * kW4Rows * kW4K * 2 + (size_t)kW4NSB * kW4BN * kW4K + 2 * kW4BN * 16;   // scale area: max(3 dword slots, 2 chunk slots)
-    auto kern = grouped_gemm_w4_kernel<GATED>;
-    static bool attr_set = false;
-    if (!attr_set) {
+    const bool stream = w4_use_stream(A, E);
+    const int tile_rows = stream ? kS4Rows : kW4Rows;
+    const size_t lds_bytes = stream ? (size_t)kS4NSA * kS4Rows * kW4K * 2 + (size_t)2 * kW4BN * 128
+                                    : (size_t)kW4NSA * kW4Rows * kW4K * 2 + (size_t)kW4NSB * kW4BN * kW4K +
+                                          2 * kW4BN * 16;   // scale area: max(3 dword slots, 2 chunk slots)
+    const bool odd = ((K / 2) >> 5) & 1;     // row bytes an odd multiple of 32
+    auto kern = stream ? (odd ? grouped_gemm_w4_stream_kernel<GATED, true> : grouped_gemm_w4_stream_kernel<GATED, false>)
+                       : grouped_gemm_w4_kernel<GATED>;
+    static bool attr_set[3] = {false, false, false};
+    const int which = stream ? (odd ? 2 : 1) : 0;
+    if (!attr_set[which]) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return e;
-        attr_set = true;
+        attr_set[which] = true;
     }
     const int64_t n_tiles = (N + NO - 1) / NO;
-    const int64_t m_tiles_max = (A + kW4Rows - 1) / kW4Rows + (A < E ? A : E);
+    const int64_t m_tiles_max = (A + tile_rows - 1) / tile_rows + (A < E ? A : E);
     const int64_t grid = ((m_tiles_max * n_tiles + 7) / 8) * 8;
     if (grid >= ((int64_t)1 << 31)) return hipErrorInvalidValue;   // the device-side tile search counts in 32 bits
-    kern<<<(unsigned)grid, kW4Waves * 64, lds_bytes, s>>>(X, ldx, row_map, map_div, offsets, E, W, S, rows_per_expert, N, K,
+    kern<<<(unsigned)grid, (stream ? kS4Waves : kW4Waves) * 64, lds_bytes, s>>>(X, ldx, row_map, map_div, offsets, E, W, S, rows_per_expert, N, K,
                                                           Out, ldo);
     return hipGetLastError();
 }
@@ -362,6 +753,11 @@ hipError_t launch_ffn_down_w4(const void* act, const int32_t* offsets, int64_t A
 {
     return launch_w4<false>(single_src(act), I, nullptr, 1, offsets, E, A, w_down, s_down, (int64_t)H, H, I,
                             (bf16_t*)y_perm, H, s);
+}
+
+const char* ffn_w4_variant_name(int64_t A, int E)
+{
+    return w4_use_stream(A, E) ? "grouped_gemm_w4_stream_kernel<gated>" : "grouped_gemm_w4_kernel<gated>";
 }
 
 }  // namespace moe

@@ -36,8 +36,11 @@ SHAPES = [
 ]
 
 
+# both kernel shapes on every case (the library would pick one by the batch's rows per expert)
+@pytest.mark.parametrize("variant", ["w4_tile64", "w4_stream"])
 @pytest.mark.parametrize("w", SHAPES, ids=[w.name for w in SHAPES])
-def test_single_layer_steps(gpu_lib, w):
+def test_single_layer_steps(gpu_lib, w, variant, monkeypatch):
+    monkeypatch.setenv("MOE_FFN_VARIANT", variant)
     L = inputs.make_layer(w, 0)
     Ld, Ln = dev_layer(L), inputs.layer_to_numpy(L)
     xd, xp = inputs.make_hidden(w)
