@@ -46,7 +46,8 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16_kernel(
     const TileCoord tc = find_tile<BM>(offsets, E, n_tiles);
     if (!tc.valid) return;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform: what depends on it stays in scalar registers
     const int wm = wave >> 1, wn = wave & 1;
     const int n0 = tc.n_tile * NO;
     const bf16_t* We = W + (int64_t)tc.expert * w_expert_stride;
@@ -214,7 +215,8 @@ __global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
     const TileCoord tc = find_tile<BM>(offsets, E, n_tiles);
     if (!tc.valid) return;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform: what depends on it stays in scalar registers
     const int wm = wave / WN, wn = wave % WN;
     const int n0 = tc.n_tile * NO;
     const bf16_t* We = W + (int64_t)tc.expert * w_expert_stride;

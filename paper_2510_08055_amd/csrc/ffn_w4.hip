@@ -361,10 +361,10 @@ __global__ __launch_bounds__(kW4Waves * 64, 2) void grouped_gemm_w4_kernel(
 // The load schedule is therefore fixed, with nothing to keep count of.  Every stage issues the same
 // loads: [the activations of stage g + 3,] then line ((c + g) / 4) + 1 of the rows whose class c has
 // (c + g) % 4 = 0; the start-up issues what stages -3, -2, -1 would have.  Past a row's end the rule
-// simply fetches the next line of memory (the next row's bytes, into the line slot the row has
-// left for good), past the last stage the activation load repeats the last stage into a free slot:
-// harmless, and the loads in flight at the top of a stage are always the same, so the wait count is
-// a constant (row bytes an odd multiple of 32: one line load per stage) or one of four (else).
+// fetches the row's last line once more (into the line slot the row has left for good), past the
+// last stage the activation load repeats the last stage into a free slot: harmless and served by
+// the caches, and the loads in flight at the top of a stage are always the same, so the wait count
+// is a constant (row bytes an odd multiple of 32: one line load per stage) or one of four (else).
 // Loads return in order, so the wait for the activations of stage g also covers every line issued
 // before them: the activation ring (4 stages) runs as far ahead as the lines do.  The scale bytes
 // never touch LDS: a lane needs one byte per stage for its weight row and holds them in registers
@@ -455,7 +455,7 @@ __global__ __launch_bounds__(kS4Waves * 64, 4) void grouped_gemm_w4_stream_kerne
         return ((i >> 1) & 1) | (xq << 1);
     };
     const uint8_t* b_src[B_LPW];       // this lane's 16 bytes of line 0
-    int cls[B_LPW];                    // the load's class (wave-uniform; = k when ODD)
+    int cls[B_LPW], lmax[B_LPW];       // the load's class (wave-uniform; = k when ODD) and its rows' last line
     bool clamp_any = false;            // some address this wave will ask for lies outside W (wave-uniform)
 #pragma unroll
     for (int k = 0; k < B_LPW; ++k) {
@@ -465,9 +465,9 @@ __global__ __launch_bounds__(kS4Waves * 64, 4) void grouped_gemm_w4_stream_kerne
         const int phase = (int)((uintptr_t)row & 127);
         b_src[k] = row - phase + (((lane & 7) ^ line_sw(t)) << 4);
         cls[k] = ODD ? k : __builtin_amdgcn_readfirstlane(phase >> 5);
-        // the first line may begin in front of W; the last line asked for is ((cls + nk - 1) / 4) + 1
-        const int l_last = ((cls[k] + nk - 1) >> 2) + 1;
-        clamp_any = clamp_any || __ballot(b_src[k] < W || b_src[k] + (int64_t)l_last * 128 > W_last) != 0;
+        lmax[k] = (cls[k] + nk - 1) >> 2;
+        // the first line may begin in front of W, the last one may end behind it
+        clamp_any = clamp_any || __ballot(b_src[k] < W || b_src[k] + (int64_t)lmax[k] * 128 > W_last) != 0;
     }
     // this lane's operand row: tile row 32 wave + fr, k-half fq of every stage
     const int fr = lane & 31, fq = lane >> 5;
@@ -527,7 +527,10 @@ __global__ __launch_bounds__(kS4Waves * 64, 4) void grouped_gemm_w4_stream_kerne
         for (int k = 0; k < B_LPW; ++k) {
             if (ODD ? ((k + g) & 3) != 0 : ((cls[k] + g) & 3) != 0) continue;
             const int L = ((cls[k] + g) >> 2) + 1;
-            const uint8_t* a = b_src[k] + (int64_t)L * 128;
+            // past the row's last line the load repeats that line (it has just been fetched: no memory
+            // traffic), still into the slot the rule names, which the row has left for good
+            const int Lsrc = L < lmax[k] ? L : lmax[k];
+            const uint8_t* a = b_src[k] + (int64_t)Lsrc * 128;
             if (clamp_any) a = a > W_last ? W_last : a;      // (only the wave that holds the last rows of W)
             __builtin_amdgcn_global_load_lds((glb_ptr_t*)a,
                                              (lds_ptr_t*)(smem + B_BASE + (L & 1) * B_SLOT + (wave * B_LPW + k) * 1024),
