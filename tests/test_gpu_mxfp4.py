@@ -33,6 +33,10 @@ SHAPES = [
                     residual=False, weight_format="mxfp4"),           # 5 and 3 k-stages, ragged n-tiles, 64+ rows per expert
     inputs.Workload("w4_sparse", H=2880, E=32, K=4, I=2880 // 5 * 1 // 64 * 64, n_layers=1, D=7, P=0, dtype="bf16",
                     seed=63, residual=False, weight_format="mxfp4"),  # 45 k-stages, most experts with 0-2 rows
+    inputs.Workload("w4_deep", H=4160, E=4, K=2, I=128, n_layers=1, D=3, P=20, dtype="bf16", seed=65, residual=False,
+                    weight_format="mxfp4"),   # 65 k-stages: more than 128 scale bytes per row; rows of 2080 bytes (odd multiple of 32)
+    inputs.Workload("w4_deep_even", H=4224, E=4, K=2, I=192, n_layers=1, D=0, P=37, dtype="bf16", seed=66,
+                    residual=False, weight_format="mxfp4"),   # 66 k-stages, rows of 2112 bytes (phases 0 and 64 only)
 ]
 
 
