@@ -24,7 +24,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA
 BOUND = {"qwen3_layer": "hbm", "decode_large": "hbm", "qwen3_group8": None, "mixtral_zipf": "mfma", "tiny_f32": "hbm",
          "gptoss_layer": "hbm",       # 264 rows per expert: below the ridge of ~312 flop/B
-         "decode_large_w4": "hbm"}
+         "decode_large_w4": "hbm",
+         "gptoss_layer_w4": "mfma"}   # 17/32 byte per weight moves the ridge to ~1200 flop/B... 264 rows per expert = 994 flop/B: near it; priced as the bf16 MFMA GEMM it is
 
 
 def parse_args():

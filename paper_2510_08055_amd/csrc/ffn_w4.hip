@@ -7,17 +7,18 @@
 // 32 consecutive elements along k.  A dequantised weight is exactly representable in bf16, so the GEMM
 // is the bf16 MFMA GEMM of ffn.hip on weights widened on the fly (v_cvt_scalef32_pk_bf16_fp4).
 //
-// One kernel shape, the weight-streaming one: 64-row x 256-weight-row tiles, 4 waves side by side along
-// the weight rows (each widens and multiplies its own 64 weight rows against the tile's one or two
-// 32-row blocks: widening the weights is the ALU work of a decode batch, so it is spread over all four
-// SIMDs), 64 k-values per stage; activation rows come through a 2-stage LDS ring as in ffn.hip.  The packed weight
-// rows and their scale bytes are fetched for TWO stages at a time (64 bytes of codes and 4 scale bytes
-// per row) into a ring of 3 such double stages: the layer is bound by the number of memory requests,
-// not their bytes, when every row contributes 32 + 2 bytes per stage (measured: 2.7x slower).  72 KB of
-// LDS: two blocks share a compute unit.
-// Within a 64-wide stage lane (row, q) feeds k-block q (32 values) to four successive MFMAs, 8 values
-// each; the activation fragments follow the same k assignment.  Any fixed assignment is a valid
-// summation order; this kernel is the only 4-bit variant, so every schedule sees the same one.
+// Two kernel shapes.  The first, for batches with more than 32 rows per expert on average: 64-row x
+// 256-weight-row tiles, 4 waves side by side along the weight rows (each widens and multiplies its own
+// 64 weight rows against the tile's one or two 32-row blocks), 64 k-values per stage; activation rows
+// come through a 2-stage LDS ring as in ffn.hip.  The packed weight rows and their scale bytes are
+// fetched for TWO stages at a time (64 bytes of codes and 4 scale bytes per row) into a ring of 3 such
+// double stages: the layer is bound by the number of memory requests, not their bytes, when every row
+// contributes 32 + 2 bytes per stage (measured: 2.7x slower).  72 KB of LDS: two blocks share a compute
+// unit.  The second, the weight-streaming shape for decode-heavy batches, is described further down.
+// In both, within a 64-wide stage lane (row, q) feeds k-block q (32 values) to four successive MFMAs, 8
+// values each, and the activation fragments follow the same k assignment; stages and MFMAs run in the
+// same ascending order, so the two shapes produce bit-identical results and a chunked and a layered pass
+// may pick different ones.
 #include <cstdlib>
 #include <cstring>
 

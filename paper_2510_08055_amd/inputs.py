@@ -63,6 +63,9 @@ WORKLOADS = {
                              dtype="bf16", chunk=512, seed=5, residual=False),
     # 4-bit expert weights (Table 7 runs a model with fp4 expert weights): the decode-heavy shape again, the
     # expert weights in MXFP4, so a pass streams 17/64 of the bf16 bytes
+    # the second model family as it ships: MXFP4 expert weights under the hybrid batch of gptoss_layer
+    "gptoss_layer_w4": Workload("gptoss_layer_w4", H=2880, E=32, K=4, I=2880, n_layers=1, D=64, P=2048,
+                                dtype="bf16", chunk=512, seed=7, residual=False, weight_format="mxfp4"),
     "decode_large_w4": Workload("decode_large_w4", H=2880, E=128, K=4, I=2880, n_layers=4, D=256, P=0,
                                 dtype="bf16", chunk=512, seed=6, weight_format="mxfp4"),
 }

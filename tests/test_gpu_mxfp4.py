@@ -78,6 +78,23 @@ def test_single_layer_steps(gpu_lib, w, variant, monkeypatch):
         assert torch.equal(torch.cat([yd2, yp2]), y)
 
 
+def test_kernel_shapes_bit_identical(gpu_lib, monkeypatch):
+    """Chunked and layered passes may pick different kernel shapes: their results must not differ by a bit."""
+    for w in SHAPES[1:3]:
+        L = dev_layer(inputs.make_layer(w, 0))
+        xd, xp = inputs.make_hidden(w)
+        x = torch.cat([xd, xp]).to(DEV)
+        ctx = make_ctx(gpu_lib, w, w.D + w.P)
+        idx, _ = ctx.moe_router_topk(x, L["w_router"])
+        _, offsets, _, _, x_perm = ctx.moe_permute(x, idx)
+        out = {}
+        for variant in ("w4_tile64", "w4_stream"):
+            monkeypatch.setenv("MOE_FFN_VARIANT", variant)
+            out[variant] = ctx.moe_grouped_ffn_mxfp4(x_perm, offsets, L["w_gate_up"], L["s_gate_up"], L["w_down"],
+                                                     L["s_down"]).clone()
+        assert torch.equal(out["w4_tile64"], out["w4_stream"]), w.name
+
+
 def test_group_with_residual_teacher_forced(gpu_lib):
     w = inputs.Workload("w4_group", H=256, E=8, K=2, I=192, n_layers=3, D=6, P=90, dtype="bf16", seed=64,
                         weight_format="mxfp4")
@@ -133,3 +150,29 @@ def test_decode_large_w4_full_size_sampled(gpu_lib):
     assert_close(y[torch.from_numpy(rows).to(DEV)], o_y, "bf16", "decode_large_w4", mag=np.abs(o_y) + mag)
     active = len(set(o_idx.reshape(-1).tolist()))
     assert c.active_experts_total == active and c.expert_bytes == active * 3 * w.H * w.I * 17 // 32
+
+
+def test_gptoss_layer_w4_full_size_sampled(gpu_lib):
+    """The hybrid batch of the second model family with its 4-bit expert weights (64-row tile shape)."""
+    w = inputs.WORKLOADS["gptoss_layer_w4"]
+    xd, xp = inputs.make_hidden(w, device=DEV)
+    ctx = make_ctx(gpu_lib, w, w.D + w.P)
+    L = inputs.make_layer(w, 0, device=DEV)
+    Ln = inputs.layer_to_numpy(L)
+    ctx.moe_reset_counters()
+    yd, yp = ctx.moe_group_forward([L], xd, xp, "layered")
+    c = ctx.moe_read_counters()
+    y = torch.cat([yd, yp])
+    x = torch.cat([xd, xp])
+    xn = inputs.to_numpy(x)
+    o_idx, _ = oracle.router_topk(xn, Ln["w_router"], None, w.K)
+    idx, _ = ctx.moe_router_topk(x, L["w_router"])
+    assert (idx.cpu().numpy() == o_idx).all()
+    rows = np.array([0, 63, 64, 1111, w.D + w.P - 1])
+    o_y, _, _, mag = oracle_layer(w, Ln, xn, w.residual, rows)
+    assert_close(y[torch.from_numpy(rows).to(DEV)], o_y, "bf16", "gptoss_layer_w4", mag=np.abs(o_y) + mag)
+    active = len(set(o_idx.reshape(-1).tolist()))
+    assert c.active_experts_total == active and c.expert_bytes == active * 3 * w.H * w.I * 17 // 32
+    # the chunked schedule (streaming shape on the small chunks) gives the same bits
+    yd2, yp2 = ctx.moe_group_forward([L], xd, xp, "chunked", 128)
+    assert torch.equal(torch.cat([yd2, yp2]), y)
