@@ -176,3 +176,35 @@ def test_gptoss_layer_w4_full_size_sampled(gpu_lib):
     # the chunked schedule (streaming shape on the small chunks) gives the same bits
     yd2, yp2 = ctx.moe_group_forward([L], xd, xp, "chunked", 128)
     assert torch.equal(torch.cat([yd2, yp2]), y)
+
+
+@pytest.mark.parametrize("variant", ["w4_tile64", "w4_stream"])
+@pytest.mark.parametrize("H,I,E,rows", [
+    (128, 192, 6, [32, 0, 33, 1, 64, 65]),        # whole and just-over row blocks, an empty expert, one row
+    (448, 64, 3, [0, 0, 70]),                     # leading empty experts; 224-byte rows (phases 0 / 96 / 64 / 32)
+    (2880, 2880, 2, [9, 40]),                     # the decode shape: 45 stages, ragged last n-tile
+])
+def test_grouped_ffn_is_the_dense_swiglu_of_each_expert(gpu_lib, H, I, E, rows, variant, monkeypatch):
+    monkeypatch.setenv("MOE_FFN_VARIANT", variant)
+    A = sum(rows)
+    w = inputs.Workload("f4", H=H, E=E, K=1, I=I, n_layers=1, D=0, P=A, dtype="bf16", seed=67, weight_format="mxfp4")
+    L = inputs.make_layer(w, 0)
+    # (rows of spread 0.5: uniformly drawn FP4 codes make heavier weights than the N(0, 0.02) of the bf16
+    # recipe, and with unit rows the 2880-wide case has outputs of magnitude ~10, where bf16 rounding of
+    # the intermediate alone exceeds the absolute bound)
+    x_perm = inputs.randn((A, H), 0.5, 67, "x_perm", 0, "bf16")
+    offsets = torch.tensor(np.concatenate([[0], np.cumsum(rows)]), dtype=torch.int32)
+    ctx = make_ctx(gpu_lib, w, A)
+    y = ctx.moe_grouped_ffn_mxfp4(x_perm.to(DEV), offsets.to(DEV), L["w_gate_up"].to(DEV), L["s_gate_up"].to(DEV),
+                                  L["w_down"].to(DEV), L["s_down"].to(DEV))
+    ref = np.zeros((A, H))
+    mag = np.zeros((A, H))
+    ones = inputs.to_numpy(torch.ones((1, H), dtype=torch.bfloat16))
+    for e in range(E):
+        lo, hi = int(offsets[e]), int(offsets[e + 1])
+        if hi > lo:   # a one-expert MoE layer is that expert's dense FFN with weight 1
+            ref[lo:hi], _, _, mag[lo:hi] = oracle.moe_layer(
+                inputs.to_numpy(x_perm[lo:hi]), ones, None, inputs.to_numpy(L["w_gate_up"][e:e + 1]),
+                inputs.to_numpy(L["w_down"][e:e + 1]), 1, want_mag=True,
+                s_gate_up=inputs.to_numpy(L["s_gate_up"][e:e + 1]), s_down=inputs.to_numpy(L["s_down"][e:e + 1]))
+    assert_close(y, ref, "bf16", "grouped_ffn_mxfp4", mag=np.abs(ref) + mag)
