@@ -18,16 +18,44 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 
+# Kernels in these files issue loads from inline asm whose results are picked up after an explicit wait.
+# The register allocator takes such a result for ready at once: if it ever spilled one, it would save a
+# register the load has not written yet, and the load would later land on whatever the register holds by
+# then (an address, say).  So these kernels must compile without any scratch memory; the build checks it.
+NO_SCRATCH = {"router.hip": ("router_logits_kernel",), "ffn_w4.hip": ("grouped_gemm_w4_stream_kernel",)}
+
+
+def _scratch_users(log, names):
+    """Kernels (mangled names containing one of `names`) whose resource remarks report scratch or spills."""
+    bad, cur = [], None
+    for line in log.splitlines():
+        if "remark: Function Name:" in line:
+            cur = line.split("Function Name:")[1].split()[0]
+        elif cur and any(n in cur for n in names):
+            for key in ("ScratchSize [bytes/lane]:", "VGPRs Spill:"):
+                if key in line and int(line.split(key)[1].split()[0]) != 0:
+                    bad.append(f"{cur}: {key} {line.split(key)[1].split()[0]}")
+    return bad
+
+
 def _compile(src, verbose):
     out = os.path.join(OBJ, src.replace(".hip", ".o"))
-    cmd = ["hipcc", *FLAGS, "-c", os.path.join(CSRC, src), "-o", out]
+    extra = ["-Rpass-analysis=kernel-resource-usage"] if src in NO_SCRATCH else []
+    cmd = ["hipcc", *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", out]
     if verbose:
         print(" ".join(cmd), flush=True)
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    # the host pass does not know the GPU-only target feature; that warning is expected
-    log = "\n".join(l for l in r.stdout.splitlines() if "packed-fp32-ops" not in l)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed on {src}:\n{r.stdout}")
+    if src in NO_SCRATCH:
+        bad = _scratch_users(r.stdout, NO_SCRATCH[src])
+        if bad:
+            raise RuntimeError(f"{src}: kernels with asynchronous register loads must not use scratch memory:\n  "
+                               + "\n  ".join(bad))
+    # the host pass does not know the GPU-only target feature (that warning is expected); the resource
+    # remarks are only read by the check above
+    log = "\n".join(l for l in r.stdout.splitlines()
+                    if "packed-fp32-ops" not in l and "kernel-resource-usage" not in l)
     if verbose and log.strip():
         print(log, flush=True)
     return out

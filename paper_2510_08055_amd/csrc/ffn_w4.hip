@@ -76,6 +76,16 @@ __device__ __forceinline__ bf16x8_t widen_fp4x8(uint32_t v, float scale)
 // E8M0 scale byte -> float 2^(s - 127); s = 0 is 2^-127, a subnormal float.
 __device__ __forceinline__ float e8m0_to_float(uint32_t s) { return __uint_as_float(s ? s << 23 : 0x00400000u); }
 
+// The same for byte SH / 8 of a word, in three instructions: the byte is moved into the exponent field
+// in place, and 2^-127 = 0x00400000 exceeds the result only when the byte is 0.  (Written as a compare
+// and select the compiler extracts the byte twice, with three constants moved into registers per use.)
+template <int SH> __device__ __forceinline__ float e8m0_byte_to_float(uint32_t word)
+{
+    uint32_t bits = (SH <= 23 ? word << (23 - SH) : word >> (SH - 23)) & 0x7f800000u, out;
+    asm("v_max_u32 %0, %1, %2" : "=v"(out) : "s"(0x00400000u), "v"(bits));
+    return __uint_as_float(out);
+}
+
 //   Out[r, n] = sum_k X[src(r), k] * W[e, n, k]                                        (GATED = false)
 //   Out[r, n] = silu(sum_k X.. * W[e, n, k]) * (sum_k X.. * W[e, N + n, k])            (GATED = true)
 // W: packed codes [E][rows][K/2] bytes, S: scales [E][rows][K/32] bytes; rows = N (or 2N when GATED).
@@ -470,6 +480,16 @@ __global__ __launch_bounds__(kS4Waves * 64, 4) void grouped_gemm_w4_stream_kerne
         // the first line may begin in front of W, the last one may end behind it
         clamp_any = clamp_any || __ballot(b_src[k] < W || b_src[k] + (int64_t)lmax[k] * 128 > W_last) != 0;
     }
+    // ODD: the four loads of a lane differ by the same amount in every lane ((q_k - q_0) rows and the
+    // difference of the two line phases: the stand-in rows of a ragged tile keep their distance as well),
+    // so one address and three scalar offsets do, which frees six registers.
+    const uint8_t* b_lane = b_src[0];
+    int k_off[B_LPW];
+#pragma unroll
+    for (int k = 0; k < B_LPW; ++k) k_off[k] = ODD ? __builtin_amdgcn_readfirstlane((int)(b_src[k] - b_src[0])) : 0;
+    auto line_addr = [&](int k, int L) {
+        return ODD ? b_lane + (k_off[k] + L * 128) : b_src[k] + (int64_t)L * 128;
+    };
     // this lane's operand row: tile row 32 wave + fr, k-half fq of every stage
     const int fr = lane & 31, fq = lane >> 5;
     const int t_own = 32 * wave + fr;
@@ -531,8 +551,11 @@ __global__ __launch_bounds__(kS4Waves * 64, 4) void grouped_gemm_w4_stream_kerne
             // past the row's last line the load repeats that line (it has just been fetched: no memory
             // traffic), still into the slot the rule names, which the row has left for good
             const int Lsrc = L < lmax[k] ? L : lmax[k];
-            const uint8_t* a = b_src[k] + (int64_t)Lsrc * 128;
-            if (clamp_any) a = a > W_last ? W_last : a;      // (only the wave that holds the last rows of W)
+            const uint8_t* a = line_addr(k, Lsrc);
+            if (clamp_any) {      // only the wave that holds the last rows of W: a branch, not a select on every load
+                asm volatile("");
+                a = a > W_last ? W_last : a;
+            }
             __builtin_amdgcn_global_load_lds((glb_ptr_t*)a,
                                              (lds_ptr_t*)(smem + B_BASE + (L & 1) * B_SLOT + (wave * B_LPW + k) * 1024),
                                              16, 0, 0);
@@ -558,13 +581,15 @@ __global__ __launch_bounds__(kS4Waves * 64, 4) void grouped_gemm_w4_stream_kerne
     };
 
     // ---- start-up: scale bytes, line 0 of every row, then what stages -3, -2, -1 would issue ----
-    u32x4_t s_raw[8];                  // the first 8 pieces, until the row-map lookup below has returned
+    // the first 8 pieces, until the row-map lookup below has returned (a row with fewer pieces fetches its
+    // last one again: with conditional loads the compiler treats the eight values as one 32-register tuple
+    // and copies it around)
+    u32x4_t s_raw[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
-        if (i < s_row_pieces) s_raw[i] = fetch_piece(i);
+    for (int i = 0; i < 8; ++i) s_raw[i] = fetch_piece(i < s_row_pieces ? i : s_row_pieces - 1);
 #pragma unroll
     for (int k = 0; k < B_LPW; ++k) {
-        const uint8_t* a = b_src[k];
+        const uint8_t* a = line_addr(k, 0);
         if (clamp_any) {
             a = a < W ? W : a;
             a = a > W_last ? W_last : a;
@@ -577,8 +602,7 @@ __global__ __launch_bounds__(kS4Waves * 64, 4) void grouped_gemm_w4_stream_kerne
         wait_vmcnt<B_LPW>();
         asm volatile("" : "+v"(a_row_id)::"memory");
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
-            if (i < s_row_pieces) keep_piece(s_raw[i], i, s_lo[i], s_hi[i]);
+        for (int i = 0; i < 8; ++i) keep_piece(s_raw[i], i < s_row_pieces ? i : s_row_pieces - 1, s_lo[i], s_hi[i]);
         const int tr = wave * 8 + a_lrow;
         const int64_t src = row_map ? (int64_t)(a_row_id / map_div) : (int64_t)a_row_id;
         a_src = row_ptr<bf16_t>(X, src, ldx) + ((a_chunk ^ swz<64>(tr)) << 3);
@@ -587,8 +611,18 @@ __global__ __launch_bounds__(kS4Waves * 64, 4) void grouped_gemm_w4_stream_kerne
     issue_stage(-2, 1);
     issue_stage(-1, 2);
 
-    const int fsw = swz<64>(fr);
-    const int a_off = fr * A_ROWB;
+    // activation fragment j4 of this lane's token row: LDS offset inside a stage's slot (the slot's own
+    // offset is a constant of the unrolled step and goes into the instruction)
+    // (LDS addresses as integers in the LDS address space: the compiler then folds the slot into the
+    // instruction's offset field instead of adding the array's base at every read)
+    typedef __attribute__((address_space(3))) const bf16x8_t lds_bf16x8_t;
+    typedef __attribute__((address_space(3))) const u32x4_t lds_u32x4_t;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_ptr_t*)smem;
+    uint32_t a_rd[4];
+#pragma unroll
+    for (int j4 = 0; j4 < 4; ++j4) a_rd[j4] = lds0 + fr * A_ROWB + (((fq * 4 + j4) ^ swz<64>(fr)) << 4);
+    const uint32_t b_rd = lds0 + B_BASE + b_off;
+    const uint32_t b_rd_odd = b_rd + ((fq ^ (b_sw & 1)) << 4);
     // token columns past the tile's rows are never stored: their lanes skip the activation reads (with a
     // handful of rows per expert most of the LDS read traffic would be for nothing)
     const bool a_reader = fr < ((tile_rows + 7) & ~7);
@@ -617,13 +651,13 @@ __global__ __launch_bounds__(kS4Waves * 64, 4) void grouped_gemm_w4_stream_kerne
                     // counts of the next stages allow for)
 #pragma unroll
                     for (int i = 0; i < 8; i += 2) {
-                        if (chunk + i < s_row_pieces) {
-                            u32x4_t t0 = fetch_piece(chunk + i), t1 = t0;
-                            if (chunk + i + 1 < s_row_pieces) t1 = fetch_piece(chunk + i + 1);
-                            wait_vmcnt<0>();
-                            keep_piece(t0, chunk + i, s_lo[i], s_hi[i]);
-                            keep_piece(t1, chunk + i + 1, s_lo[i + 1], s_hi[i + 1]);
-                        }
+                        const int last = s_row_pieces - 1;
+                        const int p0 = chunk + i < last ? chunk + i : last;
+                        const int p1 = chunk + i + 1 < last ? chunk + i + 1 : last;
+                        u32x4_t t0 = fetch_piece(p0), t1 = fetch_piece(p1);
+                        wait_vmcnt<0>();
+                        keep_piece(t0, p0, s_lo[i], s_hi[i]);
+                        keep_piece(t1, p1, s_lo[i + 1], s_hi[i + 1]);
                     }
                 }
                 switch (chunk & 7) {
@@ -638,18 +672,29 @@ __global__ __launch_bounds__(kS4Waves * 64, 4) void grouped_gemm_w4_stream_kerne
                 }
             }
             // the operand reads go out first, the loads of this stage are issued while they return
-            const char* a_base = smem + (u & 3) * A_SLOT + a_off;
             if (a_reader) {
 #pragma unroll
                 for (int j4 = 0; j4 < 4; ++j4)
-                    af[j4] = *reinterpret_cast<const bf16x8_t*>(a_base + (((fq * 4 + j4) ^ fsw) << 4));
+                    af[j4] = *(lds_bf16x8_t*)(uintptr_t)(a_rd[j4] + (u & 3) * A_SLOT);
             }
-            const int tt = b_cls + g;
-            const int y = ((tt & 3) << 1) | fq;
-            const u32x4_t bq = *reinterpret_cast<const u32x4_t*>(smem + B_BASE + ((tt >> 2) & 1) * B_SLOT + b_off +
-                                                                 ((y ^ b_sw) << 4));
+            // stage g of this lane's row: 32-byte piece (b_cls + g) % 4 of the line in slot ((b_cls + g) / 4) % 2
+            uint32_t b_addr;
+            if (ODD) {      // (the swizzle only touches the 16-byte half: folded into b_rd_odd; one multiply puts
+                            // the piece at bits 5-6 and the slot at bit 15)
+                static_assert(B_SLOT == 1 << 15, "the slot bit");
+                b_addr = b_rd_odd + ((((uint32_t)(b_cls + u) & 7u) * 0x2020u) & 0x8060u);
+            } else {
+                const int tt = b_cls + g;
+                const int y = ((tt & 3) << 1) | fq;
+                b_addr = b_rd + ((tt >> 2) & 1) * B_SLOT + ((y ^ b_sw) << 4);
+            }
+            const u32x4_t bq = *(lds_u32x4_t*)(uintptr_t)b_addr;
             issue_stage(g, (u + NSA - 1) & 3);
-            const float sc = e8m0_to_float((((u & 4) ? s_cur_hi : s_cur_lo) >> ((u & 3) * 8)) & 0xffu);
+            const uint32_t s_word = (u & 4) ? s_cur_hi : s_cur_lo;
+            const float sc = (u & 3) == 0   ? e8m0_byte_to_float<0>(s_word)
+                             : (u & 3) == 1 ? e8m0_byte_to_float<8>(s_word)
+                             : (u & 3) == 2 ? e8m0_byte_to_float<16>(s_word)
+                                            : e8m0_byte_to_float<24>(s_word);
 #pragma unroll
             for (int j4 = 0; j4 < 4; ++j4) {
                 // weight rows as the MFMA's row operand: a lane ends up with 4 consecutive output columns

@@ -105,3 +105,17 @@ def test_binding_fails_loudly_without_the_library(monkeypatch):
     monkeypatch.setattr(binding, "LIB_PATH", "/nonexistent/libmoe_lp.so")
     with pytest.raises(RuntimeError):
         binding.load()
+
+
+def test_build_rejects_scratch_in_kernels_with_asynchronous_loads():
+    """The build reads the compiler's resource remarks and refuses a stream / router kernel that spills."""
+    from paper_2510_08055_amd import build
+    ok = ("x.hip:1:1: remark: Function Name: _ZN3moe29grouped_gemm_w4_stream_kernelILb1ELb1EEEv [-Rpass-analysis]\n"
+          "x.hip:1:1: remark:     ScratchSize [bytes/lane]: 0 [-Rpass-analysis]\n"
+          "x.hip:1:1: remark:     VGPRs Spill: 0 [-Rpass-analysis]\n")
+    assert build._scratch_users(ok, ("grouped_gemm_w4_stream_kernel",)) == []
+    bad = ok.replace("ScratchSize [bytes/lane]: 0", "ScratchSize [bytes/lane]: 836").replace("VGPRs Spill: 0", "VGPRs Spill: 2072")
+    found = build._scratch_users(bad, ("grouped_gemm_w4_stream_kernel",))
+    assert len(found) == 2 and "836" in found[0] and "2072" in found[1]
+    other = bad.replace("grouped_gemm_w4_stream_kernel", "some_other_kernel")
+    assert build._scratch_users(other, ("grouped_gemm_w4_stream_kernel",)) == []
