@@ -572,8 +572,10 @@ __global__ __launch_bounds__(kS4Waves * 64, 4) void grouped_gemm_w4_stream_kerne
     }
     auto wait_for_stage = [&](int r) {     // r = g mod 4, a compile-time constant where it is called
         if (ODD) {
-            if (a_loader) wait_vmcnt<5>();
-            else wait_vmcnt<3>();
+            // 3 line loads may be in flight for every wave; a wave that fetches activations could leave its
+            // last 2 activation loads in flight as well (5), but the stricter count costs nothing (the
+            // lines run four stages ahead, and three would do) and saves a branch in every stage
+            wait_vmcnt<3>();
         } else {
             const int n = lines_at[(r + 1) & 3] + lines_at[(r + 2) & 3] + lines_at[(r + 3) & 3] + (a_loader ? 2 : 0);
             wait_vmcnt_at_most(n);
