@@ -44,6 +44,10 @@ def parse_args():
     ap.add_argument("--groups", type=int, default=0,
                     help="--schedule stack: number of layer groups (0 = max(1, ceil(slice / --granule)), at most layers)")
     ap.add_argument("--granule", type=int, default=512, help="--schedule stack: tokens per iteration the group rule aims for")
+    ap.add_argument("--per-iteration", action="store_true",
+                    help="stack schedule with --chunk 0: also time every iteration of the step on its own (the "
+                         "iteration whose designated layer group carries the prompt, Sec. 4.1-4.2), rebuilt from "
+                         "group calls and checked against the stack driver's result")
     ap.add_argument("--decode", type=int, default=-1, help="override the workload's number of decode tokens")
     ap.add_argument("--route-skew", type=float, default=-1.0,
                     help="override the workload's router popularity skew (std of a per-expert logit bias)")
@@ -163,6 +167,54 @@ def main():
                 "kernel": variant, "kernel_avg_us": round(k_avg_s * 1e6, 2), "kernel_launches": k_n,
                 "algorithmic_bytes_per_launch": int(alg_bytes), "algorithmic_flops_per_launch": int(alg_flops)}
 
+    # ---- iteration-time balance of the layered schedule over the stack (one slice only) ----
+    iteration_ms = None
+    if stack and args.per_iteration and chunk == 0 and w.D and w.P:
+        G = args.groups if args.groups > 0 else binding.moe_num_layer_groups(w.P, w.n_layers, args.granule)
+        first = binding.moe_layer_groups(w.n_layers, G)
+        big = binding.Context(w.H, w.E, w.K, w.I, dt, max_tokens=w.D + w.P, residual=w.residual, device=dev,
+                              weight_format=w.weight_format)
+        p_state = [xp, torch.empty_like(xp)]
+        d_buf = [torch.empty_like(xd), torch.empty_like(xd)]
+
+        def iteration(g, src):       # iteration g: group g carries the prompt rows, every group the decode rows
+            d_in = xd
+            for h in range(G):
+                sub = layers[first[h]:first[h + 1]]
+                d_out = d_buf[h % 2]
+                if h == g:
+                    big.moe_group_forward(sub, d_in, p_state[src], "layered", y_decode=d_out, y_prefill=p_state[1 - src])
+                else:
+                    big.moe_group_forward(sub, d_in, None, "layered", y_decode=d_out)
+                d_in = d_out
+            return d_in
+
+        def whole_step():
+            src, d_last = 0, None
+            for g in range(G):
+                d_last = iteration(g, src)
+                src = 1 - src
+            return d_last, p_state[src]
+
+        d_last, p_last = whole_step()
+        torch.cuda.synchronize()
+        if not (torch.equal(d_last, yd) and torch.equal(p_last, yp)):
+            print("bench.py: the iterations rebuilt from group calls do not reproduce the stack driver", file=sys.stderr)
+            sys.exit(3)
+        reps = 3
+        ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(G)]
+              for _ in range(reps)]
+        for r in range(reps):
+            src = 0
+            for g in range(G):
+                ev[r][g][0].record()
+                iteration(g, src)
+                ev[r][g][1].record()
+                src = 1 - src
+        torch.cuda.synchronize()
+        iteration_ms = [round(min(ev[r][g][0].elapsed_time(ev[r][g][1]) for r in range(reps)), 4) for g in range(G)]
+        big.close()
+
     # ---- the oracle as it stands, on this host's cores, on a bounded sample of the same workload ----
     cpu = None
     if not args.no_cpu_baseline:
@@ -198,6 +250,8 @@ def main():
         "iterations_per_step": ctr.iterations // args.steps,
         "gate_up_launches_per_step": launches_per_step,
     }
+    if iteration_ms is not None:
+        out["iteration_ms"] = iteration_ms      # one entry per iteration of the step; group sizes differ by at most one layer
     print(json.dumps(out), flush=True)
 
 
