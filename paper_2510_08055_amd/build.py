@@ -38,9 +38,34 @@ def _scratch_users(log, names):
     return bad
 
 
+# Files whose kernels issue their direct-to-LDS loads from inline asm that writes M0 (the LDS base of such a
+# load).  The compiler does not honour an M0 clobber on an asm statement, so these files must hold no other
+# use of M0; the build reads the device assembly (a by-product of the same compile) and checks that M0
+# only ever appears as  s_mov_b32 m0, <sgpr> ; s_nop 0 ; global_load_lds_<size>.
+M0_ONLY_FOR_LDS_LOADS = ("ffn.hip", "ffn_w4.hip")
+
+
+def _foreign_m0_uses(asm):
+    """Lines of the device assembly that touch M0 in any way other than the asm-issued LDS loads."""
+    code = [l.strip() for l in asm.splitlines()]
+    code = [l for l in code if l and not l.startswith((";", ".", "//")) and not l.endswith(":")]
+    bad = []
+    for i, l in enumerate(code):
+        if "m0" not in l.split(";")[0].replace(",", " ").split():
+            continue
+        nxt = [c.split(";")[0].split() for c in code[i + 1:i + 3]]
+        ok = (l.split(";")[0].replace(",", " ").split()[:2] == ["s_mov_b32", "m0"] and len(nxt) == 2
+              and nxt[0] == ["s_nop", "0"] and nxt[1][0].startswith("global_load_lds_"))
+        if not ok:
+            bad.append(l)
+    return bad
+
+
 def _compile(src, verbose):
     out = os.path.join(OBJ, src.replace(".hip", ".o"))
     extra = ["-Rpass-analysis=kernel-resource-usage"] if src in NO_SCRATCH else []
+    if src in M0_ONLY_FOR_LDS_LOADS:
+        extra.append("-save-temps=obj")
     cmd = ["hipcc", *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", out]
     if verbose:
         print(" ".join(cmd), flush=True)
@@ -52,6 +77,12 @@ def _compile(src, verbose):
         if bad:
             raise RuntimeError(f"{src}: kernels with asynchronous register loads must not use scratch memory:\n  "
                                + "\n  ".join(bad))
+    if src in M0_ONLY_FOR_LDS_LOADS:
+        asm_path = os.path.join(OBJ, src.replace(".hip", "-hip-amdgcn-amd-amdhsa-gfx950.s"))
+        with open(asm_path) as f:
+            bad = _foreign_m0_uses(f.read())
+        if bad:
+            raise RuntimeError(f"{src}: M0 is used outside the asm-issued direct-to-LDS loads:\n  " + "\n  ".join(bad[:10]))
     # the host pass does not know the GPU-only target feature (that warning is expected); the resource
     # remarks are only read by the check above
     log = "\n".join(l for l in r.stdout.splitlines()

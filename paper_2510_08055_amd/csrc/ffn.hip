@@ -224,9 +224,11 @@ __global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
     const int rb_valid = (rows_here + 31) / 32;   // row blocks of this tile with at least one real row
 
     // ---- source addresses of this lane's loads: group g = wave + NW*p covers tile rows RPL*g .. RPL*g + RPL-1 ----
-    // Order matters for the start-up latency: the row-map lookups are issued first, then (without waiting
-    // for them) the weight addresses are formed and the weight stages of the prologue are put in flight,
-    // and only then are the looked-up rows turned into activation addresses.
+    // Order matters for the start-up latency: the row-map lookups are issued first, then the weight
+    // addresses are formed and the weight stages of the prologue are put in flight, and only then are the
+    // looked-up rows turned into activation addresses.  (The compiler's wait at the lookups' first use
+    // does not know of the asm-issued weight loads and asks for vmcnt(0), so it covers them as well; the
+    // first barrier needs the first weight stage anyway.)
     const int l_row = lane / CPR, l_chunk = lane % CPR;
     const int nk_ = K / PBK;
     int32_t a_row_id[A_LPW];
@@ -247,10 +249,9 @@ __global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
         if (GATED && rb >= NO) n += N;
         b_src[p] = We + (int64_t)n * K + ((l_chunk ^ swz<PBK>(rb)) << 3);
     }
+    const uint32_t lds0 = lds_address(smem);
     auto issue_b = [&](int kt, int p) {
-        __builtin_amdgcn_global_load_lds((glb_ptr_t*)(b_src[p] + kt * PBK),
-                                         (lds_ptr_t*)(smem + B_BASE + (kt % NSB) * B_SLOT + (wave + NW * p) * 1024), 16,
-                                         0, 0);
+        load_lds_16(b_src[p] + kt * PBK, lds0 + B_BASE + (kt % NSB) * B_SLOT + (wave + NW * p) * 1024);
     };
 #pragma unroll
     for (int st = 0; st < NSB - 1; ++st)
@@ -277,9 +278,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
     for (int p = 0; p < A_LPW; ++p) a_live[p] = !MASK_A || ((wave + NW * p) * RPL + l_row) < rows_here;
     auto issue_a = [&](int kt, int p) {
         if (a_live[p])
-            __builtin_amdgcn_global_load_lds((glb_ptr_t*)(a_src[p] + kt * PBK),
-                                             (lds_ptr_t*)(smem + (kt % NSA) * A_SLOT + (wave + NW * p) * 1024), 16, 0,
-                                             0);
+            load_lds_16(a_src[p] + kt * PBK, lds0 + (kt % NSA) * A_SLOT + (wave + NW * p) * 1024);
     };
     // Load q of a step: ORD 0 alternates over the parts as A0 B0 | A1 B1 ..., ORD 1 issues the activation
     // loads first, ORD 2 the weight loads first.
@@ -343,7 +342,6 @@ __global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
                 bfr[set][j] = *reinterpret_cast<const bf16x8_t*>(base_b + b_row[j] + k_off[kk]);
         };
         auto mfma_set = [&](int set) {
-            __builtin_amdgcn_s_setprio(1);
 #pragma unroll
             for (int i = 0; i < TMV; ++i)
 #pragma unroll
@@ -351,7 +349,6 @@ __global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
                     // weight rows as the MFMA's row operand, activation rows as its column operand: a lane then
                     // holds 4 consecutive OUTPUT COLUMNS of one output row, which the epilogue stores as 8 bytes
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[set][j], af[set][i], acc[i][j], 0, 0, 0);
-            __builtin_amdgcn_s_setprio(0);
         };
 
         // prologue: the weight stages are already in flight; the activation stages follow, and the first

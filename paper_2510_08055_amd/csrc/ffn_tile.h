@@ -128,6 +128,31 @@ template <int N> __device__ __forceinline__ void wait_vmcnt()
 __device__ __forceinline__ void wait_lds_reads() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 __device__ __forceinline__ void block_barrier() { asm volatile("s_barrier" ::: "memory"); }
 
+// One wave-level direct-to-LDS load: lane i's BYTES bytes from `src` land at LDS byte address lds_base + BYTES i
+// (lds_base is wave-uniform and travels in M0).  Issued from inline asm on purpose.  The compiler's
+// wait-count pass takes the builtin form for an access to both global memory and LDS, and while it
+// believes one to be in flight (it never sees the explicit vmcnt waits above, so: always) it turns
+// every LDS wait into lgkmcnt(0): an MFMA that needs the fragments read one k-slice ago then also waits
+// for the reads just issued for the next slice.  With the asm form the waits carry the exact count.
+// The kernels that use it must not leave anything else in M0 (nothing in them does: LDS instructions
+// need no M0 on this target).
+template <int BYTES> __device__ __forceinline__ void load_lds(const void* src, uint32_t lds_base)
+{
+    static_assert(BYTES == 16 || BYTES == 4 || BYTES == 2, "direct-to-LDS loads move 16, 4 or 2 bytes per lane");
+    if (BYTES == 16)
+        asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(lds_base) : "memory");
+    else if (BYTES == 4)
+        asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off" ::"v"(src), "s"(lds_base) : "memory");
+    else
+        asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_ushort %0, off" ::"v"(src), "s"(lds_base) : "memory");
+}
+__device__ __forceinline__ void load_lds_16(const void* src, uint32_t lds_base) { load_lds<16>(src, lds_base); }
+// LDS byte address of a pointer into the block's dynamic shared memory
+__device__ __forceinline__ uint32_t lds_address(const void* p)
+{
+    return (uint32_t)(uintptr_t)(lds_ptr_t*)p;
+}
+
 // Source-side swizzle of a tile row: which LDS 16-byte chunk slot holds global chunk c of row r is
 // c ^ swz(r).  Chosen so that the 16-byte operand reads of 8 (and of 16) consecutive rows fall into
 // distinct bank groups whether the LDS serves 128 or 256 bytes per clock.

@@ -114,6 +114,7 @@ __global__ __launch_bounds__(kW4Waves * 64, 2) void grouped_gemm_w4_kernel(
     static_assert((NSA - 1) * A_LPW + (NSB - 1) * (B_LPW + 1) + 2 <= 20, "wait_vmcnt_at_most covers up to 20 loads in flight");
 
     extern __shared__ __attribute__((aligned(1024))) char smem[];
+    const uint32_t ldsb = lds_address(smem);    // LDS byte address of the block's dynamic shared memory
 
     const int n_tiles = (N + NO - 1) / NO;
     const TileCoord tc = find_tile<BM>(offsets, E, n_tiles);
@@ -181,19 +182,17 @@ __global__ __launch_bounds__(kW4Waves * 64, 2) void grouped_gemm_w4_kernel(
     int issued = 0;                    // load instructions this wave has issued
     int last_b[NSB], last_a[NSA];      // `issued` right after the last load of the (double) stage in each ring slot
     auto issue_b = [&](int d) {        // double stage d = stages 2d and 2d + 1
-        char* bs = smem + B_BASE + (d % NSB) * B_SLOT;
+        const uint32_t bs = ldsb + B_BASE + (d % NSB) * B_SLOT;
         const bool tail = odd_tail && d == n_double - 1;
 #pragma unroll
         for (int p = 0; p < B_LPW; ++p)
-            if (!tail || b_first_half[p])
-                __builtin_amdgcn_global_load_lds((glb_ptr_t*)(b_src[p] + (int64_t)d * B_ROWB),
-                                                 (lds_ptr_t*)(bs + (wave + NW * p) * 1024), 16, 0, 0);
+            if (!tail || b_first_half[p]) load_lds<16>(b_src[p] + (int64_t)d * B_ROWB, bs + (wave + NW * p) * 1024);
         issued += B_LPW;     // (every wave has lanes on both sides of the tail mask, so both loads are always issued)
         if (!wide_scales) {
-            lds_ptr_t* dst = (lds_ptr_t*)(smem + S_BASE + (d % NSB) * S_SLOT + wave * 256);
-            if (!tail) __builtin_amdgcn_global_load_lds((glb_ptr_t*)(s_src + d * 4), dst, 4, 0, 0);
-            else if (row_scales >= 4) __builtin_amdgcn_global_load_lds((glb_ptr_t*)(s_src + row_scales - 4), dst, 4, 0, 0);
-            else __builtin_amdgcn_global_load_lds((glb_ptr_t*)s_src, dst, 2, 0, 0);
+            const uint32_t dst = ldsb + S_BASE + (d % NSB) * S_SLOT + wave * 256;
+            if (!tail) load_lds<4>(s_src + d * 4, dst);
+            else if (row_scales >= 4) load_lds<4>(s_src + row_scales - 4, dst);
+            else load_lds<2>(s_src, dst);
             issued += 1;
         }
 #pragma unroll
@@ -202,8 +201,7 @@ __global__ __launch_bounds__(kW4Waves * 64, 2) void grouped_gemm_w4_kernel(
     };
     int last_s[2] = {0, 0};
     auto issue_s = [&](int c) {        // wide scale chunk c = stages 8c .. 8c + 7
-        __builtin_amdgcn_global_load_lds((glb_ptr_t*)(s_src + chunk_start(c)),
-                                         (lds_ptr_t*)(smem + S_BASE + (c & 1) * SW_SLOT + wave * 1024), 16, 0, 0);
+        load_lds<16>(s_src + chunk_start(c), ldsb + S_BASE + (c & 1) * SW_SLOT + wave * 1024);
         issued += 1;
         if (c & 1) last_s[1] = issued;
         else last_s[0] = issued;
@@ -235,9 +233,7 @@ __global__ __launch_bounds__(kW4Waves * 64, 2) void grouped_gemm_w4_kernel(
         for (int p = 0; p < A_LPW; ++p) {
             if ((wave + NW * p) * 8 >= tile_rows) continue;
             if ((wave + NW * p) * 8 + a_lrow < tile_rows)
-                __builtin_amdgcn_global_load_lds((glb_ptr_t*)(a_src[p] + kt * PBK),
-                                                 (lds_ptr_t*)(smem + (kt % NSA) * A_SLOT + (wave + NW * p) * 1024), 16, 0,
-                                                 0);
+                load_lds<16>(a_src[p] + kt * PBK, ldsb + (kt % NSA) * A_SLOT + (wave + NW * p) * 1024);
             issued += 1;
         }
 #pragma unroll
@@ -412,6 +408,7 @@ __global__ __launch_bounds__(kS4Waves * 64, 4) void grouped_gemm_w4_stream_kerne
     static_assert(BM == 32 && BN == 32 * NW && B_LPW == 4 && NSA == 4, "tile configuration");
 
     extern __shared__ __attribute__((aligned(1024))) char smem[];
+    const uint32_t ldsb = lds_address(smem);    // LDS byte address of the block's dynamic shared memory
 
     const int n_tiles = (N + NO - 1) / NO;
     const TileCoord tc = find_tile<BM>(offsets, E, n_tiles);
@@ -541,8 +538,7 @@ __global__ __launch_bounds__(kS4Waves * 64, 4) void grouped_gemm_w4_stream_kerne
         if (a_loader) {
             const int kt = g + NSA - 1 < nk ? g + NSA - 1 : nk - 1;
             if (wave * 8 + a_lrow < tile_rows)
-                __builtin_amdgcn_global_load_lds((glb_ptr_t*)(a_src + kt * PBK),
-                                                 (lds_ptr_t*)(smem + a_slot * A_SLOT + wave * 1024), 16, 0, 0);
+                load_lds<16>(a_src + kt * PBK, ldsb + a_slot * A_SLOT + wave * 1024);
         }
 #pragma unroll
         for (int k = 0; k < B_LPW; ++k) {
@@ -556,9 +552,7 @@ __global__ __launch_bounds__(kS4Waves * 64, 4) void grouped_gemm_w4_stream_kerne
                 asm volatile("");
                 a = a > W_last ? W_last : a;
             }
-            __builtin_amdgcn_global_load_lds((glb_ptr_t*)a,
-                                             (lds_ptr_t*)(smem + B_BASE + (L & 1) * B_SLOT + (wave * B_LPW + k) * 1024),
-                                             16, 0, 0);
+            load_lds<16>(a, ldsb + B_BASE + (L & 1) * B_SLOT + (wave * B_LPW + k) * 1024);
         }
     };
     // Loads in flight at the top of stage g that stage g does not need: the lines of stages g-3, g-2, g-1
@@ -596,7 +590,7 @@ __global__ __launch_bounds__(kS4Waves * 64, 4) void grouped_gemm_w4_stream_kerne
             a = a < W ? W : a;
             a = a > W_last ? W_last : a;
         }
-        __builtin_amdgcn_global_load_lds((glb_ptr_t*)a, (lds_ptr_t*)(smem + B_BASE + (wave * B_LPW + k) * 1024), 16, 0, 0);
+        load_lds<16>(a, ldsb + B_BASE + (wave * B_LPW + k) * 1024);
     }
     {
         // the row-map load and the scale pieces came before the 4 line loads: wait for them, cut the pieces

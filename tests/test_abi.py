@@ -119,3 +119,22 @@ def test_build_rejects_scratch_in_kernels_with_asynchronous_loads():
     assert len(found) == 2 and "836" in found[0] and "2072" in found[1]
     other = bad.replace("grouped_gemm_w4_stream_kernel", "some_other_kernel")
     assert build._scratch_users(other, ("grouped_gemm_w4_stream_kernel",)) == []
+
+
+def test_build_rejects_m0_uses_outside_the_asm_issued_lds_loads():
+    """The direct-to-LDS loads write M0 from inline asm; the build refuses assembly that touches M0 otherwise."""
+    from paper_2510_08055_amd import build
+    ok = ("\ts_add_i32 s17, s34, s9\n"
+          "\ts_mov_b32 m0, s17\n"
+          "\ts_nop 0\n"
+          "\tglobal_load_lds_dwordx4 v[222:223], off\n"
+          "\t;;#ASMEND\n"
+          "\ts_mov_b32 m0, s4 ; comment\n"
+          "\ts_nop 0\n"
+          "\tglobal_load_lds_ushort v[2:3], off\n"
+          "\tv_mfma_f32_32x32x16_bf16 v[0:15], v[16:19], v[20:23], v[0:15]\n")
+    assert build._foreign_m0_uses(ok) == []
+    # the compiler's own forms: an add into M0, M0 as a source, a write that no LDS load follows
+    assert len(build._foreign_m0_uses(ok.replace("s_mov_b32 m0, s17", "s_add_i32 m0, s37, s31"))) == 1
+    assert len(build._foreign_m0_uses(ok + "\tv_readlane_b32 s3, v5, m0\n")) == 1
+    assert len(build._foreign_m0_uses(ok.replace("\tglobal_load_lds_ushort v[2:3], off\n", "\tds_read_b32 v1, v2\n"))) == 1
