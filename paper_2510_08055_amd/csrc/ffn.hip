@@ -200,12 +200,18 @@ __global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
     constexpr int NSMIN = NSA < NSB ? NSA : NSB, NSMAX = NSA < NSB ? NSB : NSA;
     static_assert(PBK == 64 || PBK == 32, "stage depth must be 64 or 32");
     static_assert(RBM % WM == 0 && TM <= 4 && TNO >= 1 && NSA >= 2 && NSB >= 2, "bad tile configuration");
-    static_assert(ORD == 0 ? NSA == NSB : ORD == 1 ? (NSB >= NSA) : (NSA >= NSB), "the shallower ring loads first");
+    static_assert(ORD == 0 ? NSA == NSB : ORD == 1 ? (NSB >= NSA) : ORD == 2 ? (NSA >= NSB) : (NSA + 1 == NSB),
+                  "the shallower ring loads first");
+    // ORD 3: the activation ring is one stage shallower than the weight ring, and all activation loads of
+    // stage g+NSA are issued at once, right behind the barrier at the end of step g that frees their slot
+    // (before the last MFMAs of that step); only the weight loads are spread over the next step.  The
+    // activation loads then have a whole step to land instead of half a step.
+    constexpr bool A_EARLY = (ORD == 3);
     static_assert(BM % (RPL * NW) == 0 && BN % (RPL * NW) == 0, "tile rows must split evenly over the waves");
     // In a step the loads of activation stage g+NSA-1 are issued first, those of weight stage g+NSB-1
     // after them; loads return in issue order, so when stage g+1 is needed the loads that may still be
     // in flight are the ones issued after activation stage g+1.
-    constexpr int WAIT_MAIN = (NSMIN - 2) * LPS + (NSA < NSB ? B_LPW : NSB < NSA ? A_LPW : 0);
+    constexpr int WAIT_MAIN = ORD == 3 ? B_LPW : (NSMIN - 2) * LPS + (NSA < NSB ? B_LPW : NSB < NSA ? A_LPW : 0);
     constexpr int WAIT_FIRST = (NSA - 2) * A_LPW;   // prologue: all weight stages, then the activation stages
     static_assert(WAIT_MAIN < 64 && WAIT_FIRST < 64, "vmcnt is a 6-bit counter");
 
@@ -272,7 +278,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
     // the activation loads issued first, no wait count includes an activation load, so it does not matter
     // whether a fully masked load instruction is issued or branched around.  The LDS rows they would have
     // filled feed only accumulator rows that are never stored.
-    constexpr bool MASK_A = (NSA == 2 && ORD == 1);
+    constexpr bool MASK_A = (NSA == 2 && (ORD == 1 || ORD == 3));
     bool a_live[A_LPW];
 #pragma unroll
     for (int p = 0; p < A_LPW; ++p) a_live[p] = !MASK_A || ((wave + NW * p) * RPL + l_row) < rows_here;
@@ -286,6 +292,12 @@ __global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
     auto load_idx = [](int q) { return ORD == 2 ? (q >= B_LPW ? q - B_LPW : q) : (q < A_LPW ? q : q - A_LPW); };
     auto load_part = [](int q) { return ORD == 0 ? q % KS : q * KS / LPS; };
     auto issue_part = [&](int g, int part, bool more_a, bool more_b) {
+        if (A_EARLY) {
+#pragma unroll
+            for (int p = 0; p < B_LPW; ++p)
+                if (p * KS / B_LPW == part && more_b) issue_b(g + NSB - 1, p);
+            return;
+        }
 #pragma unroll
         for (int q = 0; q < LPS; ++q) {
             if (load_part(q) != part) continue;
@@ -361,6 +373,10 @@ __global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
         if (nk_ >= NSA - 1) wait_vmcnt<WAIT_FIRST>();
         else wait_vmcnt<0>();
         block_barrier();
+        if (A_EARLY && NSA - 1 < nk_) {
+#pragma unroll
+            for (int p = 0; p < A_LPW; ++p) issue_a(NSA - 1, p);
+        }
         read_frags(0, 0, 0);
         // One k-step.  MORE_A / MORE_B: activation stage g+NSA-1 / weight stage g+NSB-1 exists and is
         // loaded (in parts, between the MFMAs) into the slot stage g-1 used, free since the last
@@ -386,6 +402,10 @@ __global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
         };
         auto parts_in = [&](int part, bool more_a, bool more_b) {
             int n = 0;
+            if (A_EARLY) {
+                for (int p = 0; p < B_LPW; ++p) n += (p * KS / B_LPW == part) && more_b;
+                return n;
+            }
             for (int q = 0; q < LPS; ++q)
                 if (load_part(q) == part) n += load_is_a(q) ? more_a : more_b;
             return n;
@@ -402,11 +422,15 @@ __global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
             }
             issue_part(g, KS - 1, MORE_A, MORE_B);
             if (NEXT) {
-                if (MORE_A && MORE_B) wait_vmcnt<WAIT_MAIN>();
+                if (A_EARLY ? MORE_B : (MORE_A && MORE_B)) wait_vmcnt<WAIT_MAIN>();
                 else wait_vmcnt<0>();        // the pipeline drains: wait for everything
                 // all of this wave's reads of stage g have returned before its slots may be refilled
                 wait_lds_reads();
                 block_barrier();
+                if (A_EARLY && MORE_A) {
+#pragma unroll
+                    for (int p = 0; p < A_LPW; ++p) issue_a(g + NSA, p);
+                }
                 read_frags(g + 1, 0, 0);
             }
             mfma_set((KS - 1) & 1);
@@ -419,7 +443,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
         for (; g < n_main; ++g) step(g, T{}, T{}, T{});
         for (; g < nk_ - 1; ++g) {
             // only the shallower ring may still have a stage to fetch
-            if (NSA < NSB && g + NSA - 1 < nk_) step(g, T{}, F{}, T{});
+            if (!A_EARLY && NSA < NSB && g + NSA - 1 < nk_) step(g, T{}, F{}, T{});
             else if (NSB < NSA && g + NSB - 1 < nk_) step(g, F{}, T{}, T{});
             else step(g, F{}, F{}, T{});
         }
@@ -608,7 +632,7 @@ static hipError_t launch_bf16(RowSrc X, int ldx, const int32_t* row_map, int map
         case V_PIPE_SMALL:
             return launch_pipe<2, 128, 2, 3, 3, 64, 2, 4, 0, GATED>(X, ldx, row_map, map_div, offsets, E, A, W, w_expert_stride, N, K, Out, ldo, s);
         case V_PIPE_BIG:
-            return launch_pipe<8, 256, 2, 2, 3, 64, 2, 8, 1, GATED>(X, ldx, row_map, map_div, offsets, E, A, W, w_expert_stride, N, K, Out, ldo, s);
+            return launch_pipe<8, 256, 2, 2, 3, 64, 2, 8, 3, GATED>(X, ldx, row_map, map_div, offsets, E, A, W, w_expert_stride, N, K, Out, ldo, s);
         default:
             return launch_tile<128, 128, GATED>(X, ldx, row_map, map_div, offsets, E, A, W, w_expert_stride, N, K, Out,
                                                 ldo, s);
@@ -647,7 +671,7 @@ const char* ffn_variant_name(int dtype, int64_t A, int E, int H, int I)
     if (dtype != MOE_BF16) return "grouped_gemm_f32_kernel<gated>";
     switch (pick_variant(A, E, H)) {
         case V_PIPE_SMALL: return "grouped_gemm_bf16_pipe_kernel<2,128,2,3,3,64,2,4,0,gated>";
-        case V_PIPE_BIG: return "grouped_gemm_bf16_pipe_kernel<8,256,2,2,3,64,2,8,1,gated>";
+        case V_PIPE_BIG: return "grouped_gemm_bf16_pipe_kernel<8,256,2,2,3,64,2,8,3,gated>";
         default: return "grouped_gemm_bf16_kernel<128,128,gated>";
     }
 }
