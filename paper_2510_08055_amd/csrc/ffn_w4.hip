@@ -620,7 +620,8 @@ __global__ __launch_bounds__(kS4Waves * 64, 4) void grouped_gemm_w4_stream_kerne
     const uint32_t b_rd = lds0 + B_BASE + b_off;
     const uint32_t b_rd_odd = b_rd + ((fq ^ (b_sw & 1)) << 4);
     // token columns past the tile's rows are never stored: their lanes skip the activation reads (with a
-    // handful of rows per expert most of the LDS read traffic would be for nothing)
+    // handful of rows per expert most of the LDS read traffic would be for nothing; reading them anyway
+    // measured 3 % slower)
     const bool a_reader = fr < ((tile_rows + 7) & ~7);
 
     float16_t acc;
@@ -667,12 +668,8 @@ __global__ __launch_bounds__(kS4Waves * 64, 4) void grouped_gemm_w4_stream_kerne
                     default: s_cur_lo = s_lo[7]; s_cur_hi = s_hi[7]; break;
                 }
             }
-            // the operand reads go out first, the loads of this stage are issued while they return
-            if (a_reader) {
-#pragma unroll
-                for (int j4 = 0; j4 < 4; ++j4)
-                    af[j4] = *(lds_bf16x8_t*)(uintptr_t)(a_rd[j4] + (u & 3) * A_SLOT);
-            }
+            // the operand reads go out first (the weight piece before the activation fragments: the conversions
+            // start from it), the loads of this stage are issued while they return
             // stage g of this lane's row: 32-byte piece (b_cls + g) % 4 of the line in slot ((b_cls + g) / 4) % 2
             uint32_t b_addr;
             if (ODD) {      // (the swizzle only touches the 16-byte half: folded into b_rd_odd; one multiply puts
@@ -685,6 +682,11 @@ __global__ __launch_bounds__(kS4Waves * 64, 4) void grouped_gemm_w4_stream_kerne
                 b_addr = b_rd + ((tt >> 2) & 1) * B_SLOT + ((y ^ b_sw) << 4);
             }
             const u32x4_t bq = *(lds_u32x4_t*)(uintptr_t)b_addr;
+            if (a_reader) {
+#pragma unroll
+                for (int j4 = 0; j4 < 4; ++j4)
+                    af[j4] = *(lds_bf16x8_t*)(uintptr_t)(a_rd[j4] + (u & 3) * A_SLOT);
+            }
             issue_stage(g, (u + NSA - 1) & 3);
             const uint32_t s_word = (u & 4) ? s_cur_hi : s_cur_lo;
             const float sc = (u & 3) == 0   ? e8m0_byte_to_float<0>(s_word)
@@ -694,10 +696,14 @@ __global__ __launch_bounds__(kS4Waves * 64, 4) void grouped_gemm_w4_stream_kerne
 #pragma unroll
             for (int j4 = 0; j4 < 4; ++j4) {
                 // weight rows as the MFMA's row operand: a lane ends up with 4 consecutive output columns
-                const bf16x8_t wv = widen_fp4x8(bq[j4], sc);
+                bf16x8_t wv = widen_fp4x8(bq[j4], sc);
+                // This wave's reads of stage g must have returned before it reaches the next barrier.  The wait
+                // hangs on the last widened operand: placed after the loop it would have no data dependence
+                // on the conversions and the scheduler would hoist it above them, so that they waited for
+                // the activation fragments as well as for the weight piece they need.
+                if (j4 == 3) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(wv)::"memory");
                 acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv, af[j4], acc, 0, 0, 0);
             }
-            wait_lds_reads();   // this wave's reads of stage g have returned before it reaches the next barrier
         }
     }
     // The line and activation loads of the last stages are still in flight; nothing reads them, but the
