@@ -22,7 +22,8 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
 # The register allocator takes such a result for ready at once: if it ever spilled one, it would save a
 # register the load has not written yet, and the load would later land on whatever the register holds by
 # then (an address, say).  So these kernels must compile without any scratch memory; the build checks it.
-NO_SCRATCH = {"router.hip": ("router_logits_kernel",), "ffn_w4.hip": ("grouped_gemm_w4_stream_kernel",)}
+NO_SCRATCH = {"router.hip": ("router_logits_kernel",), "ffn_w4.hip": ("grouped_gemm_w4_stream_kernel",),
+              "ffn.hip": ("grouped_gemm_bf16_pipe_kernel",)}
 
 
 def _scratch_users(log, names):
@@ -61,6 +62,50 @@ def _foreign_m0_uses(asm):
     return bad
 
 
+# Kernels of these files load single dwords into registers from inline asm (`global_load_dword vN, ...`
+# between the compiler's #ASMSTART / #ASMEND markers) and pick the value up after an explicit
+# `s_waitcnt vmcnt`.  In the assembly, nothing between such a load and the next vmcnt wait may name vN.
+ASYNC_DWORD_LOADS = {"ffn.hip": "grouped_gemm_bf16_pipe_kernel"}
+
+
+def _early_uses_of_async_loads(asm, kernel):
+    """Instructions that name the destination of an asm-issued global_load_dword before the next vmcnt wait,
+    in every function whose (mangled) name contains `kernel`; the scan follows the listing, not the branches."""
+    import re
+    bad, cur, in_asm, pending = [], None, False, {}
+    for line in asm.splitlines():
+        m = re.match(r"^(_Z\S+):", line)
+        if m:
+            cur, in_asm, pending = (m.group(1) if kernel in m.group(1) else None), False, {}
+            continue
+        if cur is None:
+            continue
+        if "#ASMSTART" in line:
+            in_asm = True
+            continue
+        if "#ASMEND" in line:
+            in_asm = False
+            continue
+        code = line.split(";")[0].strip()
+        if not code or code.startswith(".") or code.endswith(":"):
+            continue
+        if "s_waitcnt" in code and "vmcnt" in code:
+            pending = {}
+            continue
+        named = set(int(r) for r in re.findall(r"\bv(\d+)\b", code))
+        for lo, hi in re.findall(r"\bv\[(\d+):(\d+)\]", code):
+            named.update(range(int(lo), int(hi) + 1))
+        hit = sorted(named & set(pending))
+        m = re.match(r"global_load_dword v(\d+), v\[", code) if in_asm else None
+        if m:
+            hit = [r for r in hit if r != int(m.group(1))]
+        if hit:
+            bad.append(f"{cur[:60]}...: v{hit[0]} (loaded asynchronously) named by: {code}")
+        if m:
+            pending[int(m.group(1))] = True
+    return bad
+
+
 def _compile(src, verbose):
     out = os.path.join(OBJ, src.replace(".hip", ".o"))
     extra = ["-Rpass-analysis=kernel-resource-usage"] if src in NO_SCRATCH else []
@@ -83,6 +128,12 @@ def _compile(src, verbose):
             bad = _foreign_m0_uses(f.read())
         if bad:
             raise RuntimeError(f"{src}: M0 is used outside the asm-issued direct-to-LDS loads:\n  " + "\n  ".join(bad[:10]))
+        if src in ASYNC_DWORD_LOADS:
+            with open(asm_path) as f:
+                bad = _early_uses_of_async_loads(f.read(), ASYNC_DWORD_LOADS[src])
+            if bad:
+                raise RuntimeError(f"{src}: an asynchronously loaded register is used before its wait:\n  "
+                                   + "\n  ".join(bad[:10]))
     # the host pass does not know the GPU-only target feature (that warning is expected); the resource
     # remarks are only read by the check above
     log = "\n".join(l for l in r.stdout.splitlines()

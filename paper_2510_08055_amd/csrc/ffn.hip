@@ -181,7 +181,7 @@ template <int RBM, int BN, int WM, int NSA, int NSB, int PBK, int MINW, int NW, 
 __global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
     RowSrc X, int ldx, const int32_t* __restrict__ row_map, int map_div,
     const int32_t* __restrict__ offsets, int E, const bf16_t* __restrict__ W, int64_t w_expert_stride, int N, int K,
-    bf16_t* __restrict__ Out, int ldo)
+    bf16_t* __restrict__ Out, int ldo, int a_rows)
 {
     constexpr int BM = RBM * 32, WN = NW / WM;   // NW waves arranged WM (rows) x WN (columns)
     constexpr int NO = GATED ? BN / 2 : BN;     // output columns per block
@@ -230,19 +230,24 @@ __global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
     const int rb_valid = (rows_here + 31) / 32;   // row blocks of this tile with at least one real row
 
     // ---- source addresses of this lane's loads: group g = wave + NW*p covers tile rows RPL*g .. RPL*g + RPL-1 ----
-    // Order matters for the start-up latency: the row-map lookups are issued first, then the weight
-    // addresses are formed and the weight stages of the prologue are put in flight, and only then are the
-    // looked-up rows turned into activation addresses.  (The compiler's wait at the lookups' first use
-    // does not know of the asm-issued weight loads and asks for vmcnt(0), so it covers them as well; the
-    // first barrier needs the first weight stage anyway.)
+    // Order matters for the start-up latency: the row-map lookups are issued first, then (without waiting
+    // for them) the weight addresses are formed and the weight stages of the prologue are put in flight,
+    // and only then are the looked-up rows turned into activation addresses.
     const int l_row = lane / CPR, l_chunk = lane % CPR;
     const int nk_ = K / PBK;
-    int32_t a_row_id[A_LPW];
+    // The lookups are loads issued from inline asm, picked up after an explicit wait further down: a
+    // lookup through the compiler would be waited for with vmcnt(0) (it does not know of the asm-issued
+    // weight loads that follow), i.e. together with the first weight stages out of HBM.  Until that wait
+    // the destination registers hold nothing; they are not touched in between.  Without a row map the
+    // load reads a valid dummy word (offsets[0]) and its result is ignored.
+    int32_t a_own[A_LPW], a_row_id[A_LPW];
 #pragma unroll
     for (int p = 0; p < A_LPW; ++p) {
         int r = tc.row0 + (wave + NW * p) * RPL + l_row;
         if (r >= tc.row_end) r = tc.row_end - 1;
-        a_row_id[p] = row_map ? row_map[r] : r;
+        a_own[p] = r;
+        const int32_t* src = row_map ? row_map + r : offsets;
+        asm volatile("global_load_dword %0, %1, off" : "=v"(a_row_id[p]) : "v"(src) : "memory");
     }
     const bf16_t* b_src[B_LPW];
 #pragma unroll
@@ -264,6 +269,17 @@ __global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
         if (st < nk_)
 #pragma unroll
             for (int p = 0; p < B_LPW; ++p) issue_b(st, p);
+    // the lookups came before the weight loads of the prologue: wait for them alone
+    if (nk_ >= NSB - 1) wait_vmcnt<(NSB - 1) * B_LPW>();
+    else wait_vmcnt<0>();
+#pragma unroll
+    for (int p = 0; p < A_LPW; ++p) {
+        asm volatile("" : "+v"(a_row_id[p])::"memory");
+        // a row map holds indices below a_rows; the clamp keeps a bad entry from becoming a wild address
+        int32_t id = a_row_id[p] < 0 ? 0 : a_row_id[p];
+        id = id < a_rows ? id : a_rows - 1;
+        a_row_id[p] = row_map ? id : a_own[p];
+    }
     const bf16_t* a_src[A_LPW];
 #pragma unroll
     for (int p = 0; p < A_LPW; ++p) {
@@ -615,7 +631,7 @@ static hipError_t launch_pipe(RowSrc X, int ldx, const int32_t* row_map, int map
     const int64_t grid = ((m_tiles_max * n_tiles + 7) / 8) * 8;
     if (grid >= ((int64_t)1 << 31)) return hipErrorInvalidValue;   // the device-side tile search counts in 32 bits
     kern<<<(unsigned)grid, NW * 64, lds_bytes, s>>>(X, ldx, row_map, map_div, offsets, E, W, w_expert_stride, N, K, Out,
-                                                ldo);
+                                                ldo, (int)A);
     return hipGetLastError();
 }
 

@@ -138,3 +138,28 @@ def test_build_rejects_m0_uses_outside_the_asm_issued_lds_loads():
     assert len(build._foreign_m0_uses(ok.replace("s_mov_b32 m0, s17", "s_add_i32 m0, s37, s31"))) == 1
     assert len(build._foreign_m0_uses(ok + "\tv_readlane_b32 s3, v5, m0\n")) == 1
     assert len(build._foreign_m0_uses(ok.replace("\tglobal_load_lds_ushort v[2:3], off\n", "\tds_read_b32 v1, v2\n"))) == 1
+
+
+def test_build_rejects_use_of_an_asynchronously_loaded_register_before_its_wait():
+    """Row-map lookups are asm-issued loads awaited explicitly; the build scans the listing for early uses."""
+    from paper_2510_08055_amd import build
+    ok = ("_ZN3moe29grouped_gemm_bf16_pipe_kernelILi8EEEv:\n"
+          "\tv_add_u32_e32 v13, 1, v2\n"
+          "\t;;#ASMSTART\n"
+          "\tglobal_load_dword v13, v[4:5], off\n"
+          "\t;;#ASMEND\n"
+          "\tv_add_u32_e32 v3, 1, v2\n"
+          "\t;;#ASMSTART\n"
+          "\ts_mov_b32 m0, s4\n\ts_nop 0\n\tglobal_load_lds_dwordx4 v[6:7], off\n"
+          "\t;;#ASMEND\n"
+          "\t;;#ASMSTART\n"
+          "\ts_waitcnt vmcnt(1)\n"
+          "\t;;#ASMEND\n"
+          "\tv_max_i32_e32 v13, 0, v13\n")
+    assert build._early_uses_of_async_loads(ok, "grouped_gemm_bf16_pipe_kernel") == []
+    for early in ("\tv_mov_b32_e32 v20, v13\n", "\tscratch_store_dword off, v13, off\n", "\tv_pk_add_u16 v[12:13], v[2:3], v[2:3]\n"):
+        bad = ok.replace("\tv_add_u32_e32 v3, 1, v2\n", early)
+        found = build._early_uses_of_async_loads(bad, "grouped_gemm_bf16_pipe_kernel")
+        assert len(found) == 1 and "v13" in found[0]
+    # other functions of the file are not looked at
+    assert build._early_uses_of_async_loads(bad.replace("pipe_kernel", "tile_kernel"), "grouped_gemm_bf16_pipe_kernel") == []
