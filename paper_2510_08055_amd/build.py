@@ -65,7 +65,7 @@ def _foreign_m0_uses(asm):
 # Kernels of these files load single dwords into registers from inline asm (`global_load_dword vN, ...`
 # between the compiler's #ASMSTART / #ASMEND markers) and pick the value up after an explicit
 # `s_waitcnt vmcnt`.  In the assembly, nothing between such a load and the next vmcnt wait may name vN.
-ASYNC_DWORD_LOADS = {"ffn.hip": "grouped_gemm_bf16_pipe_kernel"}
+ASYNC_DWORD_LOADS = {"ffn.hip": "grouped_gemm_bf16_pipe_kernel", "ffn_w4.hip": "grouped_gemm_w4_stream_kernel"}
 
 
 def _early_uses_of_async_loads(asm, kernel):

@@ -94,7 +94,7 @@ template <bool GATED>
 __global__ __launch_bounds__(kW4Waves * 64, 2) void grouped_gemm_w4_kernel(
     RowSrc X, int ldx, const int32_t* __restrict__ row_map, int map_div, const int32_t* __restrict__ offsets, int E,
     const uint8_t* __restrict__ W, const uint8_t* __restrict__ S, int64_t rows_per_expert, int N, int K,
-    bf16_t* __restrict__ Out, int ldo)
+    bf16_t* __restrict__ Out, int ldo, int a_rows)
 {
     constexpr int BM = kW4Rows, BN = kW4BN, NW = kW4Waves, NSA = kW4NSA, NSB = kW4NSB, PBK = kW4K;
     constexpr int WN = NW;                      // the waves sit side by side along the weight rows
@@ -116,6 +116,7 @@ __global__ __launch_bounds__(kW4Waves * 64, 2) void grouped_gemm_w4_kernel(
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     const uint32_t ldsb = lds_address(smem);    // LDS byte address of the block's dynamic shared memory
 
+    (void)a_rows;     // (same parameter list as the streaming kernel, which clamps its asynchronous row-map lookup with it)
     const int n_tiles = (N + NO - 1) / NO;
     const TileCoord tc = find_tile<BM>(offsets, E, n_tiles);
     if (!tc.valid) return;
@@ -397,7 +398,7 @@ template <bool GATED, bool ODD>
 __global__ __launch_bounds__(kS4Waves * 64, 4) void grouped_gemm_w4_stream_kernel(
     RowSrc X, int ldx, const int32_t* __restrict__ row_map, int map_div, const int32_t* __restrict__ offsets, int E,
     const uint8_t* __restrict__ W, const uint8_t* __restrict__ S, int64_t rows_per_expert, int N, int K,
-    bf16_t* __restrict__ Out, int ldo)
+    bf16_t* __restrict__ Out, int ldo, int a_rows)
 {
     constexpr int BM = kS4Rows, BN = kW4BN, NW = kS4Waves, NSA = kS4NSA, PBK = kW4K;
     constexpr int NO = GATED ? BN / 2 : BN;     // output columns per block
@@ -597,6 +598,10 @@ __global__ __launch_bounds__(kS4Waves * 64, 4) void grouped_gemm_w4_stream_kerne
         // down to this lane's bytes
         wait_vmcnt<B_LPW>();
         asm volatile("" : "+v"(a_row_id)::"memory");
+        if (row_map) {      // a row map holds indices below a_rows; the clamp keeps a bad entry from becoming a wild address
+            a_row_id = a_row_id < 0 ? 0 : a_row_id;
+            a_row_id = a_row_id < a_rows ? a_row_id : a_rows - 1;
+        }
 #pragma unroll
         for (int i = 0; i < 8; ++i) keep_piece(s_raw[i], i < s_row_pieces ? i : s_row_pieces - 1, s_lo[i], s_hi[i]);
         const int tr = wave * 8 + a_lrow;
@@ -786,7 +791,7 @@ hipError_t launch_w4(RowSrc X, int ldx, const int32_t* row_map, int map_div, con
     const int64_t grid = ((m_tiles_max * n_tiles + 7) / 8) * 8;
     if (grid >= ((int64_t)1 << 31)) return hipErrorInvalidValue;   // the device-side tile search counts in 32 bits
     kern<<<(unsigned)grid, (stream ? kS4Waves : kW4Waves) * 64, lds_bytes, s>>>(X, ldx, row_map, map_div, offsets, E, W, S, rows_per_expert, N, K,
-                                                          Out, ldo);
+                                                          Out, ldo, (int)A);
     return hipGetLastError();
 }
 
