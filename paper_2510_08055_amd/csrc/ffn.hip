@@ -208,9 +208,10 @@ __global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
     // activation loads then have a whole step to land instead of half a step.
     constexpr bool A_EARLY = (ORD == 3);
     static_assert(BM % (RPL * NW) == 0 && BN % (RPL * NW) == 0, "tile rows must split evenly over the waves");
-    // In a step the loads of activation stage g+NSA-1 are issued first, those of weight stage g+NSB-1
-    // after them; loads return in issue order, so when stage g+1 is needed the loads that may still be
-    // in flight are the ones issued after activation stage g+1.
+    // ORD 0-2: in a step the loads of activation stage g+NSA-1 are issued first, those of weight stage
+    // g+NSB-1 after them; loads return in issue order, so when stage g+1 is needed the loads that may
+    // still be in flight are the ones issued after activation stage g+1.  ORD 3: activation stage g+1 went
+    // out behind the previous barrier, before the weight loads of step g, which are the B_LPW that may stay.
     constexpr int WAIT_MAIN = ORD == 3 ? B_LPW : (NSMIN - 2) * LPS + (NSA < NSB ? B_LPW : NSB < NSA ? A_LPW : 0);
     constexpr int WAIT_FIRST = (NSA - 2) * A_LPW;   // prologue: all weight stages, then the activation stages
     static_assert(WAIT_MAIN < 64 && WAIT_FIRST < 64, "vmcnt is a 6-bit counter");
@@ -303,7 +304,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
             load_lds_16(a_src[p] + kt * PBK, lds0 + (kt % NSA) * A_SLOT + (wave + NW * p) * 1024);
     };
     // Load q of a step: ORD 0 alternates over the parts as A0 B0 | A1 B1 ..., ORD 1 issues the activation
-    // loads first, ORD 2 the weight loads first.
+    // loads first, ORD 2 the weight loads first; with ORD 3 a step's parts hold its weight loads only.
     auto load_is_a = [](int q) { return ORD == 2 ? q >= B_LPW : q < A_LPW; };
     auto load_idx = [](int q) { return ORD == 2 ? (q >= B_LPW ? q - B_LPW : q) : (q < A_LPW ? q : q - A_LPW); };
     auto load_part = [](int q) { return ORD == 0 ? q % KS : q * KS / LPS; };
