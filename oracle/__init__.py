@@ -87,10 +87,28 @@ def _check(rc, what):
                           f"({ {1: 'bad argument', 2: 'non-finite logit', 3: 'allocation'}.get(rc, '?')})")
 
 
+def _round(a, fmt):
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    out = np.empty_like(a)
+    lib().orc_round_array(_p(a), ctypes.c_int64(a.size), int(fmt), _p(out))
+    return out
+
+
 def round_bf16(a):
     """Round float64 values to the nearest bfloat16 (ties to even); returns float64."""
-    f = np.vectorize(lib().orc_round_bf16, otypes=[np.float64])
-    return f(np.asarray(a, dtype=np.float64))
+    return _round(a, BF16)
+
+
+def round_f32(a):
+    """Round float64 values to the nearest binary32 (ties to even); returns float64."""
+    return _round(a, F32)
+
+
+def bf16_bits(a):
+    """uint16 bit patterns of float64 values that are exactly representable in bfloat16 (e.g. round_bf16's)."""
+    f = np.ascontiguousarray(a, dtype=np.float64).astype(np.float32)
+    assert (f.astype(np.float64) == a).all() and ((f.view(np.uint32) & 0xFFFF) == 0).all(), "not bfloat16 values"
+    return (f.view(np.uint32) >> 16).astype(np.uint16)
 
 
 def router_topk(x, w_router, bias, k, renormalize=True, want_logits=False, want_gap=False):

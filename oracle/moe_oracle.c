@@ -96,6 +96,13 @@ static double round_to_format(double v, int sig, int emin, int emax)
 double orc_round_bf16(double v) { return round_to_format(v, 8, -126, 127); }
 double orc_round_f32(double v) { return round_to_format(v, 24, -126, 127); }
 
+/* The same, element by element over an array (fmt: ORC_BF16 or ORC_F32; anything else copies). */
+void orc_round_array(const double *in, int64_t n, int fmt, double *out)
+{
+    for (int64_t i = 0; i < n; ++i)
+        out[i] = (fmt == ORC_BF16) ? orc_round_bf16(in[i]) : (fmt == ORC_F32) ? orc_round_f32(in[i]) : in[i];
+}
+
 /* ------------------------------------------------------------------------
  * Router for one token (Sec. 2.4): logits, top-k selection, mixing weights.
  * z must have room for E doubles.  Returns ORC_ERR_NONFINITE on a NaN/inf

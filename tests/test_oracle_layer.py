@@ -164,6 +164,56 @@ def test_round_bf16_matches_the_library_cast_and_hand_cases():
     assert oracle.round_bf16([tie_plus])[0] == 1.0 + 2.0 ** -7
 
 
+def test_round_f32_matches_numpy_casts_hand_ties_and_subnormals():
+    """The fp32 rounding used between the layers of an fp32 group, pinned to numpy's double -> float32 cast
+    (IEEE round to nearest even, done by the hardware conversion) and to hand-derived cases."""
+    # hand cases: exact ties between neighbouring binary32 values go to the even 24-bit significand
+    ulp = 2.0 ** -23
+    cases = [1.0 + ulp / 2, 1.0 + 3 * ulp / 2, -(1.0 + ulp / 2), 1.0 + ulp / 2 + 2.0 ** -50, 1.0 + ulp / 4,
+             2.0 ** 127 * (2 - 2.0 ** -24),           # halfway between the largest finite float and 2^128: overflows
+             2.0 ** -149 * 0.5, 2.0 ** -149 * 1.5, 2.0 ** -149 * 0.75,           # subnormals: spacing 2^-149 throughout
+             2.0 ** -127 + 2.0 ** -150, 2.0 ** -127 + 2.0 ** -150 + 2.0 ** -170]      # a tie (2^-127 = even 2^22 steps) and just above it
+    want = [1.0, 1.0 + 2 * ulp, -1.0, 1.0 + ulp, 1.0, float("inf"), 0.0, 2.0 ** -148, 2.0 ** -149, 2.0 ** -127,
+            2.0 ** -127 + 2.0 ** -149]
+    assert oracle.round_f32(cases).tolist() == want
+    # ~5000 random doubles over the whole binary32 exponent range, subnormals included, plus exact floats
+    rng = np.random.default_rng(16)
+    v = rng.standard_normal(5000) * np.exp2(rng.uniform(-152, 127, 5000))
+    with np.errstate(over="ignore"):
+        ref = v.astype(np.float32).astype(np.float64)
+    assert np.isfinite(ref).all() and (np.abs(ref) < 2.0 ** -126).sum() > 50      # the sample does reach the subnormals
+    assert (oracle.round_f32(v) == ref).all()
+    f = (rng.standard_normal(1000) * np.exp2(rng.uniform(-100, 100, 1000))).astype(np.float32).astype(np.float64)
+    assert (oracle.round_f32(f) == f).all()                                       # representable values are fixed points
+    # the array form is the scalar function applied element by element
+    one = np.array([oracle.lib().orc_round_f32(float(t)) for t in v[:200]])
+    assert (one == ref[:200]).all()
+
+
+def test_fp32_group_rounds_between_layers_only():
+    """A group whose activations are held in fp32 between layers: the oracle's group driver must equal the
+    chain layer -> round_f32 -> layer written out here, and differ from the unrounded chain."""
+    rng = np.random.default_rng(17)
+    layers = []
+    for _ in range(3):
+        wr, wgu, wd = _rand_layer(rng, 6, 24, 16)
+        layers.append({"w_router": wr.astype(np.float32), "router_bias": None,
+                       "w_gate_up": wgu.astype(np.float32), "w_down": wd.astype(np.float32)})
+    x = rng.standard_normal((11, 24)).astype(np.float32)
+    yd, yp, _ = oracle.group_forward(layers, x[:3], x[3:], 2, "layered")
+    cur = x.astype(np.float64)
+    plain = x.astype(np.float64)
+    for l, L in enumerate(layers):
+        y, _, _ = oracle.moe_layer(cur, L["w_router"].astype(np.float64), None, L["w_gate_up"].astype(np.float64),
+                                   L["w_down"].astype(np.float64), 2, residual=True)
+        cur = y.astype(np.float32).astype(np.float64) if l + 1 < len(layers) else y
+        plain, _, _ = oracle.moe_layer(plain, L["w_router"].astype(np.float64), None, L["w_gate_up"].astype(np.float64),
+                                       L["w_down"].astype(np.float64), 2, residual=True)
+    got = np.concatenate([yd, yp])
+    assert (got == cur).all()
+    assert (got != plain).any() and np.abs(got - plain).max() < 1e-3
+
+
 # ------------------------------------------------------------------ schedules
 
 def _np_layers(w, n_layers=None):
