@@ -6,7 +6,9 @@
  *
  * General conventions
  *   - Every data pointer is a DEVICE pointer owned by the caller unless a
- *     parameter says "host".  Base pointers must be 16-byte aligned.
+ *     parameter says "host".  Base pointers must be 16-byte aligned; the packed
+ *     codes of MOE_W_MXFP4 expert weights must be 32-byte aligned (their scale
+ *     bytes 16, like everything else).
  *   - Tensors are dense row-major.  "dtype" elements are bfloat16 (2 bytes) or
  *     float (4 bytes) as chosen in moe_config.dtype.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
@@ -36,7 +38,8 @@ typedef enum {
     MOE_ERR_NULL = 1,      /* a required pointer is NULL */
     MOE_ERR_SHAPE = 2,     /* a size is negative / zero / inconsistent (k > E, T > max_tokens ...) */
     MOE_ERR_DTYPE = 3,     /* unknown moe_dtype */
-    MOE_ERR_ALIGN = 4,     /* H or I not a multiple of 8, or a pointer not 16-byte aligned */
+    MOE_ERR_ALIGN = 4,     /* H or I not a multiple of 8 (64 for MOE_W_MXFP4), a pointer not 16-byte aligned, or
+                              MXFP4 code bytes not 32-byte aligned */
     MOE_ERR_WORKSPACE = 5, /* workspace smaller than moe_workspace_bytes says */
     MOE_ERR_SCHEDULE = 6,  /* unknown schedule kind, or chunk <= 0 for a chunked schedule */
     MOE_ERR_DEVICE = 7     /* a HIP runtime call failed (launch error, wrong device ...) */
@@ -49,7 +52,11 @@ typedef enum { MOE_F32 = 0, MOE_BF16 = 1 } moe_dtype;
  * runs a model with fp4 expert weights) is the published OCP Microscaling format: FP4 E2M1 elements
  * (magnitudes 0, 0.5, 1, 1.5, 2, 3, 4, 6), two per byte with the even element in the low nibble, and one
  * E8M0 scale byte (2^(s-127), s in 1..254) per 32 consecutive elements of a row.  It needs dtype ==
- * MOE_BF16 (activations and the router stay bf16) and H, I multiples of 64.
+ * MOE_BF16 (activations and the router stay bf16) and H, I multiples of 64.  The code tensors (w_gate_up,
+ * w_down) must start on a 32-byte boundary: every row is then a whole number of 32-byte pieces from a
+ * 32-byte boundary, which is what lets the weight-streaming kernel fetch rows in whole aligned 128-byte
+ * lines; a 16-byte aligned pointer is refused with MOE_ERR_ALIGN before anything is launched.  The scale
+ * tensors need the general 16-byte alignment.
  */
 typedef enum { MOE_W_DTYPE = 0, MOE_W_MXFP4 = 1 } moe_weight_format;
 
@@ -63,6 +70,16 @@ typedef struct {
     int32_t renormalize; /* 1: mixing weights of the K selected experts are divided by their sum */
     int32_t residual;    /* 1: moe_group_forward links layers by x <- x + MoE(x); 0: x <- MoE(x) */
     int32_t weight_format; /* moe_weight_format of the expert weights */
+    int32_t y_perm_f32;  /* 0: the expert outputs y_perm are held in dtype between the down GEMM and the combine;
+                            1: in fp32 (bf16 contexts: one rounding fewer on the output side, for layers whose
+                            expert outputs are large against the tolerance; A*H*2 more bytes written and read
+                            per layer).  Every y_perm argument below then is a float tensor. */
+    int32_t act_split;   /* 1: the intermediate a = silu(g) * u is held as a PAIR of bf16 values, a ~ hi + lo with
+                            hi = bf16(a), lo = bf16(a - hi) (about 16 significant bits instead of 8), and the down
+                            GEMM multiplies both halves: for layers whose intermediate is so wide (I in the ten
+                            thousands) that its bf16 rounding alone exceeds the tolerance.  Doubles the down
+                            GEMM's work and the intermediate's bytes.  Needs dtype == MOE_BF16, weight_format ==
+                            MOE_W_DTYPE and y_perm_f32 == 1 (MOE_ERR_DTYPE otherwise). */
 } moe_config;
 
 /* Weights of one layer (device pointers). */
@@ -105,7 +122,7 @@ moe_status moe_create(const moe_config *cfg, int64_t max_tokens, void *workspace
 moe_status moe_destroy(moe_ctx *ctx);
 
 /*
- * Router (Sec. 2.4: "routes tokens to a small subset of ... experts, via routers").
+ * Router (Sec. 2.4).
  *   logits z[t,e] = sum_h x[t,h]*w_router[e,h] (+ bias[e]), accumulated in fp64;
  *   topk_idx[t,:] = the K experts with the largest logits, ordered by logit descending,
  *                   equal logits by ascending expert index;
@@ -134,8 +151,10 @@ moe_status moe_permute(moe_ctx *ctx, const void *x, const int32_t *topk_idx, int
  * Grouped expert FFN (Sec. 2.1: FC layers with a SwiGLU non-linearity; Sec. 2.5: each expert's
  * FC runs over the tokens routed to it).  For expert e and rows r in [offsets[e], offsets[e+1]):
  *   g = x_perm[r,:] . w_gate_up[e, 0:I, :]^T,  u = x_perm[r,:] . w_gate_up[e, I:2I, :]^T,
- *   a = g / (1 + exp(-g)) * u   (rounded once to dtype),  y_perm[r,:] = a . w_down[e]^T.
- * x_perm [A,H] dtype, offsets [E+1] int32 (device), A = offsets[E] rows -> y_perm [A,H] dtype.
+ *   a = g / (1 + exp(-g)) * u   (rounded once to dtype, or to a bf16 pair when cfg.act_split),
+ *   y_perm[r,:] = a . w_down[e]^T.
+ * x_perm [A,H] dtype, offsets [E+1] int32 (device), A = offsets[E] rows -> y_perm [A,H] dtype (float when
+ * cfg.y_perm_f32).
  * Experts with no rows cause no weight reads.  bf16 inputs accumulate in fp32 on the matrix cores.
  */
 moe_status moe_grouped_ffn(moe_ctx *ctx, const void *x_perm, const int32_t *offsets, int64_t A,
@@ -155,7 +174,8 @@ moe_status moe_grouped_ffn_mxfp4(moe_ctx *ctx, const void *x_perm, const int32_t
 /*
  * Weighted un-permute and combine (Sec. 2.4: a token's output mixes its selected experts):
  *   y[t,:] = sum_{j<K} topk_w[t,j] * y_perm[inv_perm[t*K+j], :]  (+ residual[t,:]),
- * summed in fp32 in slot order and rounded once.  residual [T,H] dtype or NULL; y may alias residual.
+ * summed in fp32 in slot order and rounded once.  y_perm [A,H] dtype (float when cfg.y_perm_f32);
+ * residual [T,H] dtype or NULL; y may alias residual.
  */
 moe_status moe_combine(moe_ctx *ctx, const void *y_perm, const int32_t *inv_perm, const float *topk_w,
                        const void *residual, int64_t T, void *y, void *stream);
@@ -240,6 +260,24 @@ moe_status moe_read_kernel_timing(moe_ctx *ctx, int32_t kernel, double *total_ms
 /* Name of the gate_up GEMM kernel variant the context would use for a batch of T rows (host string,
  * static storage): lets a benchmark label its roofline line. */
 const char *moe_ffn_variant(const moe_ctx *ctx, int64_t T);
+
+/*
+ * Test and tuning aid (not part of the method): the grouped GEMMs come in several kernel shapes, all of
+ * which compute the same bits for any batch; the library picks one from the mean rows per expert of a
+ * launch.  moe_set_ffn_variant pins the shape for every later launch on this context (MOE_FFN_AUTO
+ * restores the rule), so that tests can run every shape on every case.  A shape that cannot run the
+ * context's weight format or a launch's K (the pipelined bf16 shapes need K % 64 == 0) is ignored for
+ * that launch.  MOE_ERR_SHAPE for an unknown id.
+ */
+typedef enum {
+    MOE_FFN_AUTO = 0,
+    MOE_FFN_TILE128 = 1,    /* bf16: 128 x 128 register-staged tiles (any K) */
+    MOE_FFN_PIPE_SMALL = 2, /* bf16: 64 x 128 tiles, weight streaming */
+    MOE_FFN_PIPE_BIG = 3,   /* bf16: up to 256 x 256 tiles, compute bound */
+    MOE_FFN_W4_TILE64 = 4,  /* MXFP4: 64-row tiles */
+    MOE_FFN_W4_STREAM = 5   /* MXFP4: 32-row weight-streaming tiles */
+} moe_ffn_variant_id;
+moe_status moe_set_ffn_variant(moe_ctx *ctx, int32_t variant);
 
 const char *moe_status_string(moe_status s);
 

@@ -23,7 +23,10 @@ WEIGHT_FORMATS = {"": MOE_W_DTYPE, "dtype": MOE_W_DTYPE, "mxfp4": MOE_W_MXFP4}
 EXPORTS = ["moe_workspace_bytes", "moe_create", "moe_destroy", "moe_router_topk", "moe_permute",
            "moe_grouped_ffn", "moe_grouped_ffn_mxfp4", "moe_combine", "moe_group_forward", "moe_num_layer_groups", "moe_layer_groups",
            "moe_stack_forward", "moe_read_counters", "moe_reset_counters",
-           "moe_kernel_timing", "moe_read_kernel_timing", "moe_ffn_variant", "moe_status_string"]
+           "moe_kernel_timing", "moe_read_kernel_timing", "moe_ffn_variant", "moe_set_ffn_variant",
+           "moe_status_string"]
+
+FFN_VARIANTS = {"auto": 0, "tile128": 1, "small": 2, "big": 3, "w4_tile64": 4, "w4_stream": 5}
 
 KERNELS = {"router_logits": 0, "topk": 1, "permute": 2, "gate_up": 3, "down": 4, "combine": 5}
 
@@ -37,7 +40,8 @@ class MoeError(RuntimeError):
 class CConfig(ctypes.Structure):
     _fields_ = [("H", ctypes.c_int32), ("E", ctypes.c_int32), ("K", ctypes.c_int32), ("I", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("renormalize", ctypes.c_int32), ("residual", ctypes.c_int32),
-                ("weight_format", ctypes.c_int32)]
+                ("weight_format", ctypes.c_int32), ("y_perm_f32", ctypes.c_int32),
+                ("act_split", ctypes.c_int32)]
 
 
 class CLayer(ctypes.Structure):
@@ -98,6 +102,7 @@ def load():
     L.moe_read_kernel_timing.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64), vp]
     L.moe_ffn_variant.argtypes = [vp, i64]
     L.moe_ffn_variant.restype = ctypes.c_char_p
+    L.moe_set_ffn_variant.argtypes = [vp, i32]
     L.moe_status_string.argtypes = [i32]
     L.moe_status_string.restype = ctypes.c_char_p
     for name in EXPORTS:
@@ -123,9 +128,7 @@ def moe_num_layer_groups(prompt_len: int, n_layers: int, granule: int = 512) -> 
 
 def moe_layer_groups(n_layers: int, n_groups: int):
     """first_layer[0..n_groups]: group g holds layers first_layer[g] .. first_layer[g+1]-1."""
-    if n_groups < 0 or n_groups > 1 << 20:
-        raise MoeError(2, "moe_layer_groups")
-    out = (ctypes.c_int32 * (n_groups + 1))()
+    out = (ctypes.c_int32 * (max(int(n_groups), 0) + 1))()
     _check(load().moe_layer_groups(int(n_layers), int(n_groups), out), "moe_layer_groups")
     return list(out)
 
@@ -149,8 +152,10 @@ def _dtype_code(dt: torch.dtype) -> int:
     raise TypeError(f"unsupported dtype {dt}")
 
 
-def workspace_bytes(H, E, K, I, dtype, max_tokens, renormalize=True, residual=True, weight_format="") -> int:
-    cfg = CConfig(H, E, K, I, _dtype_code(dtype), int(renormalize), int(residual), WEIGHT_FORMATS[weight_format])
+def workspace_bytes(H, E, K, I, dtype, max_tokens, renormalize=True, residual=True, weight_format="",
+                    y_perm_f32=False, act_split=False) -> int:
+    cfg = CConfig(H, E, K, I, _dtype_code(dtype), int(renormalize), int(residual), WEIGHT_FORMATS[weight_format],
+                  int(y_perm_f32), int(act_split))
     out = ctypes.c_size_t(0)
     _check(load().moe_workspace_bytes(ctypes.byref(cfg), max_tokens, ctypes.byref(out)), "moe_workspace_bytes")
     return out.value
@@ -160,15 +165,16 @@ class Context:
     """A moe_ctx plus the torch-allocated workspace it lives on."""
 
     def __init__(self, H, E, K, I, dtype=torch.bfloat16, max_tokens=1024, renormalize=True, residual=True,
-                 device="cuda:0", weight_format=""):
+                 device="cuda:0", weight_format="", y_perm_f32=False, act_split=False):
         self.lib = load()
         self.H, self.E, self.K, self.I = H, E, K, I
         self.dtype = dtype
         self.max_tokens = max_tokens
         self.device = torch.device(device)
         self.weight_format = weight_format
+        self.y_perm_dtype = torch.float32 if y_perm_f32 else dtype
         self.cfg = CConfig(H, E, K, I, _dtype_code(dtype), int(renormalize), int(residual),
-                           WEIGHT_FORMATS[weight_format])
+                           WEIGHT_FORMATS[weight_format], int(y_perm_f32), int(act_split))
         n = ctypes.c_size_t(0)
         _check(self.lib.moe_workspace_bytes(ctypes.byref(self.cfg), max_tokens, ctypes.byref(n)),
                "moe_workspace_bytes")
@@ -214,14 +220,14 @@ class Context:
 
     def moe_grouped_ffn(self, x_perm, offsets, w_gate_up, w_down):
         A = x_perm.shape[0]
-        y_perm = torch.empty((A, self.H), dtype=self.dtype, device=self.device)
+        y_perm = torch.empty((A, self.H), dtype=self.y_perm_dtype, device=self.device)
         _check(self.lib.moe_grouped_ffn(self._ctx, _ptr(x_perm), _ptr(offsets), A, _ptr(w_gate_up), _ptr(w_down),
                                         _ptr(y_perm), _stream()), "moe_grouped_ffn")
         return y_perm
 
     def moe_grouped_ffn_mxfp4(self, x_perm, offsets, w_gate_up, s_gate_up, w_down, s_down):
         A = x_perm.shape[0]
-        y_perm = torch.empty((A, self.H), dtype=self.dtype, device=self.device)
+        y_perm = torch.empty((A, self.H), dtype=self.y_perm_dtype, device=self.device)
         _check(self.lib.moe_grouped_ffn_mxfp4(self._ctx, _ptr(x_perm), _ptr(offsets), A, _ptr(w_gate_up),
                                               _ptr(s_gate_up), _ptr(w_down), _ptr(s_down), _ptr(y_perm), _stream()),
                "moe_grouped_ffn_mxfp4")
@@ -301,3 +307,8 @@ class Context:
 
     def moe_ffn_variant(self, T: int) -> str:
         return self.lib.moe_ffn_variant(self._ctx, T).decode()
+
+    def moe_set_ffn_variant(self, variant="auto"):
+        """Pin the grouped-GEMM kernel shape of this context (a name of FFN_VARIANTS, or the id)."""
+        v = FFN_VARIANTS[variant] if isinstance(variant, str) else int(variant)
+        _check(self.lib.moe_set_ffn_variant(self._ctx, v), "moe_set_ffn_variant")

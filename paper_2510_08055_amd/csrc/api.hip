@@ -16,15 +16,19 @@ struct moe_ctx {
     // workspace slices (device)
     unsigned long long* d_active_total;
     double* logits;
-    int32_t *idx, *counts, *offsets, *perm, *inv, *tile_hist;
+    int32_t *idx, *counts, *offsets, *perm, *inv, *tile_hist, *cand_cnt;
+    uint16_t* cand;
     float* w;
     void *xa, *xb, *act, *y_perm;
     // host-side counters (everything the host already knows)
     uint64_t router_bytes, tokens_processed;
     uint32_t iterations, layer_passes;
-    // benchmark aid: HIP event pairs around the launches of the kernels selected by timing_mask
+    int ffn_variant;   // moe_ffn_variant_id pinned by moe_set_ffn_variant (MOE_FFN_AUTO: the library's rule)
+    // benchmark aid: HIP event pairs around the launches of the kernels selected by timing_mask; pairs are
+    // recycled through event_pool, so that steady-state timing creates no events
     uint32_t timing_mask;
     std::vector<std::pair<hipEvent_t, hipEvent_t>> timing[MOE_KERNEL_COUNT];
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> event_pool;
 };
 
 namespace {
@@ -40,6 +44,10 @@ moe_status check_cfg(const moe_config* c)
         return MOE_ERR_SHAPE;
     if (c->H % 8 || c->I % 8) return MOE_ERR_ALIGN;
     if (c->weight_format != MOE_W_DTYPE && c->weight_format != MOE_W_MXFP4) return MOE_ERR_DTYPE;
+    if (c->y_perm_f32 != 0 && c->y_perm_f32 != 1) return MOE_ERR_DTYPE;
+    if (c->act_split != 0 && c->act_split != 1) return MOE_ERR_DTYPE;
+    // a split intermediate: bf16 contexts with bf16 weights and fp32 expert outputs only
+    if (c->act_split && (c->dtype != MOE_BF16 || c->weight_format != MOE_W_DTYPE || !c->y_perm_f32)) return MOE_ERR_DTYPE;
     if (c->weight_format == MOE_W_MXFP4) {
         if (c->dtype != MOE_BF16) return MOE_ERR_DTYPE;
         if (c->H % 64 || c->I % 64) return MOE_ERR_ALIGN;
@@ -48,7 +56,7 @@ moe_status check_cfg(const moe_config* c)
 }
 
 struct Layout {
-    size_t counters, logits, idx, w, counts, offsets, perm, inv, tile_hist, xa, xb, act, y_perm, total;
+    size_t counters, logits, cand_cnt, cand, idx, w, counts, offsets, perm, inv, tile_hist, xa, xb, act, y_perm, total;
 };
 
 Layout carve(const moe_config& c, int64_t Tm)
@@ -60,7 +68,11 @@ Layout carve(const moe_config& c, int64_t Tm)
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o += up(bytes); return at; };
     L.counters = take(256);
-    L.logits = take((size_t)Tm * c.E * sizeof(double));
+    // the router's scratch: fp64 logits [T, E] (full fp64 pass) or candidate lists (two-pass form)
+    const bool two_pass = router_two_pass_ok(c.dtype, c.renormalize);
+    L.logits = take(two_pass ? 0 : (size_t)Tm * c.E * sizeof(double));
+    L.cand_cnt = take(two_pass ? (size_t)Tm * 4 : 0);
+    L.cand = take(two_pass ? (size_t)Tm * c.E * 2 : 0);
     L.idx = take(Am * 4);
     L.w = take(Am * 4);
     L.counts = take((size_t)c.E * 4);
@@ -70,39 +82,54 @@ Layout carve(const moe_config& c, int64_t Tm)
     L.tile_hist = take(n_tiles * c.E * 4);
     L.xa = take((size_t)Tm * c.H * esz);
     L.xb = take((size_t)Tm * c.H * esz);
-    L.act = take(Am * c.I * esz);
-    L.y_perm = take(Am * c.H * esz);
+    L.act = take(Am * c.I * esz * (c.act_split ? 2 : 1));
+    L.y_perm = take(Am * c.H * (c.y_perm_f32 ? 4 : esz));
     L.total = o;
     return L;
 }
 
-// Records an event before and after one launch when that kernel is being timed.
+// Records an event before and after one launch when that kernel is being timed.  At most kMaxTimed
+// launches per kernel are kept between two reads; later ones go untimed (the mean stays a mean).
+constexpr size_t kMaxTimed = 1 << 16;
 struct Timed {
     moe_ctx* c; int id; hipStream_t s; bool on; hipEvent_t e0, e1;
     Timed(moe_ctx* c_, int id_, hipStream_t s_) : c(c_), id(id_), s(s_), on(false), e0(nullptr), e1(nullptr)
     {
-        if (!(c->timing_mask & (1u << id))) return;
-        if (hipEventCreate(&e0) != hipSuccess) return;
-        if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return; }
+        if (!(c->timing_mask & (1u << id)) || c->timing[id].size() >= kMaxTimed) return;
+        if (!c->event_pool.empty()) {
+            e0 = c->event_pool.back().first;
+            e1 = c->event_pool.back().second;
+            c->event_pool.pop_back();
+        } else {
+            if (hipEventCreate(&e0) != hipSuccess) { e0 = nullptr; return; }
+            if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); e0 = e1 = nullptr; return; }
+        }
         on = hipEventRecord(e0, s) == hipSuccess;
     }
     ~Timed()
     {
         if (!e1) return;
         if (on && hipEventRecord(e1, s) == hipSuccess) c->timing[id].emplace_back(e0, e1);
-        else { (void)hipEventDestroy(e0); (void)hipEventDestroy(e1); }
+        else c->event_pool.emplace_back(e0, e1);
     }
 };
 
-void drop_timing(moe_ctx* c)
+// Forget the recorded launches; their events go back to the pool (or are destroyed with the context).
+void drop_timing(moe_ctx* c, bool destroy)
 {
     for (auto& v : c->timing) {
-        for (auto& p : v) { (void)hipEventDestroy(p.first); (void)hipEventDestroy(p.second); }
+        for (auto& p : v) c->event_pool.push_back(p);
         v.clear();
+    }
+    if (destroy) {
+        for (auto& p : c->event_pool) { (void)hipEventDestroy(p.first); (void)hipEventDestroy(p.second); }
+        c->event_pool.clear();
     }
 }
 
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+// the packed codes of MXFP4 weights: rows must start a multiple of 32 bytes into a 128-byte line
+inline bool misaligned32(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 31u) != 0; }
 inline moe_status dev(hipError_t e) { return e == hipSuccess ? MOE_OK : MOE_ERR_DEVICE; }
 
 // One layer on the batch `x` [T,H]; output rows [0,rows0) -> y0, the rest -> y1.
@@ -115,13 +142,19 @@ moe_status run_layer(moe_ctx* c, const moe_layer& L, RowSrc x, int64_t T, void* 
     const int n_perm_tiles = (int)((A + kPermTile - 1) / kPermTile);
     const bool fused_hist = n_perm_tiles > 1;
     hipError_t e;
-    {
+    if (router_two_pass_ok(g.dtype, g.renormalize)) {
+        // (both passes are timed as the router-logits kernel; nothing is recorded for the top-k id)
         Timed t(c, MOE_KERNEL_ROUTER_LOGITS, s);
-        e = launch_router_logits(g.dtype, x, T, g.H, L.w_router, L.router_bias, g.E, c->logits, c->tile_hist,
-                                 fused_hist ? n_perm_tiles * g.E : 0, s);
-    }
-    if (e != hipSuccess) return MOE_ERR_DEVICE;
-    {
+        e = launch_router_two_pass(x, T, g.H, L.w_router, L.router_bias, g.E, g.K, c->cand_cnt, c->cand, c->idx, c->w,
+                                   fused_hist ? c->tile_hist : nullptr, c->tile_hist, fused_hist ? n_perm_tiles * g.E : 0,
+                                   s);
+    } else {
+        {
+            Timed t(c, MOE_KERNEL_ROUTER_LOGITS, s);
+            e = launch_router_logits(g.dtype, x, T, g.H, L.w_router, L.router_bias, g.E, c->logits, c->tile_hist,
+                                     fused_hist ? n_perm_tiles * g.E : 0, s);
+        }
+        if (e != hipSuccess) return MOE_ERR_DEVICE;
         Timed t(c, MOE_KERNEL_TOPK, s);
         e = launch_topk(c->logits, T, g.E, g.K, g.renormalize, c->idx, c->w, fused_hist ? c->tile_hist : nullptr, s);
     }
@@ -137,24 +170,27 @@ moe_status run_layer(moe_ctx* c, const moe_layer& L, RowSrc x, int64_t T, void* 
     {
         Timed t(c, MOE_KERNEL_GATE_UP, s);
         if (w4)
-            e = launch_ffn_gate_up_w4(x, c->perm, g.K, c->offsets, A, g.E, g.H, g.I, (const uint8_t*)L.w_gate_up,
-                                      L.s_gate_up, c->act, s);
+            e = launch_ffn_gate_up_w4(c->ffn_variant, x, c->perm, g.K, c->offsets, A, g.E, g.H, g.I,
+                                      (const uint8_t*)L.w_gate_up, L.s_gate_up, c->act, s);
         else
-            e = launch_ffn_gate_up(g.dtype, x, c->perm, g.K, c->offsets, A, g.E, g.H, g.I, L.w_gate_up, c->act, s);
+            e = launch_ffn_gate_up(g.dtype, c->ffn_variant, g.act_split != 0, x, c->perm, g.K, c->offsets, A, g.E, g.H,
+                                   g.I, L.w_gate_up, c->act, s);
     }
     if (e != hipSuccess) return MOE_ERR_DEVICE;
     {
         Timed t(c, MOE_KERNEL_DOWN, s);
         if (w4)
-            e = launch_ffn_down_w4(c->act, c->offsets, A, g.E, g.H, g.I, (const uint8_t*)L.w_down, L.s_down, c->y_perm,
-                                   s);
+            e = launch_ffn_down_w4(c->ffn_variant, g.y_perm_f32 != 0, c->act, c->offsets, A, g.E, g.H, g.I,
+                                   (const uint8_t*)L.w_down, L.s_down, c->y_perm, s);
         else
-            e = launch_ffn_down(g.dtype, c->act, c->offsets, A, g.E, g.H, g.I, L.w_down, c->y_perm, s);
+            e = launch_ffn_down(g.dtype, c->ffn_variant, g.y_perm_f32 != 0, g.act_split != 0, c->act, c->offsets, A, g.E,
+                                g.H, g.I, L.w_down, c->y_perm, s);
     }
     if (e != hipSuccess) return MOE_ERR_DEVICE;
     {
         Timed t(c, MOE_KERNEL_COMBINE, s);
-        e = launch_combine(g.dtype, c->y_perm, c->inv, c->w, g.residual != 0, x, T, g.K, g.H, y0, rows0, y1, s);
+        e = launch_combine(g.dtype, g.y_perm_f32 != 0, c->y_perm, c->inv, c->w, g.residual != 0, x, T, g.K, g.H, y0,
+                           rows0, y1, s);
     }
     return dev(e);
 }
@@ -194,7 +230,12 @@ moe_status check_stack_args(const moe_ctx* ctx, const moe_layer* layers, int32_t
         if (!layers[l].w_router || !layers[l].w_gate_up || !layers[l].w_down) return MOE_ERR_NULL;
         if (misaligned(layers[l].w_router) || misaligned(layers[l].w_gate_up) || misaligned(layers[l].w_down))
             return MOE_ERR_ALIGN;
-        if (ctx->cfg.weight_format == MOE_W_MXFP4 && (!layers[l].s_gate_up || !layers[l].s_down)) return MOE_ERR_NULL;
+        if (ctx->cfg.weight_format == MOE_W_MXFP4) {
+            if (!layers[l].s_gate_up || !layers[l].s_down) return MOE_ERR_NULL;
+            if (misaligned32(layers[l].w_gate_up) || misaligned32(layers[l].w_down) ||
+                misaligned(layers[l].s_gate_up) || misaligned(layers[l].s_down))
+                return MOE_ERR_ALIGN;
+        }
     }
     return MOE_OK;
 }
@@ -231,6 +272,8 @@ moe_status moe_create(const moe_config* cfg, int64_t max_tokens, void* workspace
     c->esz = cfg->dtype == MOE_BF16 ? 2 : 4;
     c->d_active_total = reinterpret_cast<unsigned long long*>(b + L.counters);
     c->logits = reinterpret_cast<double*>(b + L.logits);
+    c->cand_cnt = reinterpret_cast<int32_t*>(b + L.cand_cnt);
+    c->cand = reinterpret_cast<uint16_t*>(b + L.cand);
     c->idx = reinterpret_cast<int32_t*>(b + L.idx);
     c->w = reinterpret_cast<float*>(b + L.w);
     c->counts = reinterpret_cast<int32_t*>(b + L.counts);
@@ -245,6 +288,7 @@ moe_status moe_create(const moe_config* cfg, int64_t max_tokens, void* workspace
     c->router_bytes = c->tokens_processed = 0;
     c->iterations = c->layer_passes = 0;
     c->timing_mask = 0;
+    c->ffn_variant = MOE_FFN_AUTO;
     if (hipMemsetAsync(b + L.counters, 0, 256, static_cast<hipStream_t>(stream)) != hipSuccess) {
         delete c;
         return MOE_ERR_DEVICE;
@@ -256,7 +300,7 @@ moe_status moe_create(const moe_config* cfg, int64_t max_tokens, void* workspace
 moe_status moe_destroy(moe_ctx* ctx)
 {
     if (!ctx) return MOE_ERR_NULL;
-    drop_timing(ctx);
+    drop_timing(ctx, true);
     delete ctx;
     return MOE_OK;
 }
@@ -271,6 +315,9 @@ moe_status moe_router_topk(moe_ctx* ctx, const void* x, int64_t T, const void* w
     if (misaligned(x) || misaligned(w_router)) return MOE_ERR_ALIGN;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const moe_config& g = ctx->cfg;
+    if (router_two_pass_ok(g.dtype, g.renormalize))
+        return dev(launch_router_two_pass(single_src(x), T, g.H, w_router, bias, g.E, g.K, ctx->cand_cnt, ctx->cand,
+                                          topk_idx, topk_w, nullptr, nullptr, 0, s));
     hipError_t e = launch_router_logits(g.dtype, single_src(x), T, g.H, w_router, bias, g.E, ctx->logits, nullptr, 0, s);
     if (e != hipSuccess) return MOE_ERR_DEVICE;
     return dev(launch_topk(ctx->logits, T, g.E, g.K, g.renormalize, topk_idx, topk_w, nullptr, s));
@@ -308,10 +355,11 @@ moe_status moe_grouped_ffn(moe_ctx* ctx, const void* x_perm, const int32_t* offs
     const moe_config& g = ctx->cfg;
     if (g.weight_format != MOE_W_DTYPE) return MOE_ERR_DTYPE;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    hipError_t e = launch_ffn_gate_up(g.dtype, single_src(x_perm), nullptr, 1, offsets, A, g.E, g.H, g.I, w_gate_up,
-                                      ctx->act, s);
+    hipError_t e = launch_ffn_gate_up(g.dtype, ctx->ffn_variant, g.act_split != 0, single_src(x_perm), nullptr, 1, offsets,
+                                      A, g.E, g.H, g.I, w_gate_up, ctx->act, s);
     if (e != hipSuccess) return MOE_ERR_DEVICE;
-    return dev(launch_ffn_down(g.dtype, ctx->act, offsets, A, g.E, g.H, g.I, w_down, y_perm, s));
+    return dev(launch_ffn_down(g.dtype, ctx->ffn_variant, g.y_perm_f32 != 0, g.act_split != 0, ctx->act, offsets, A, g.E,
+                               g.H, g.I, w_down, y_perm, s));
 }
 
 moe_status moe_grouped_ffn_mxfp4(moe_ctx* ctx, const void* x_perm, const int32_t* offsets, int64_t A,
@@ -323,13 +371,16 @@ moe_status moe_grouped_ffn_mxfp4(moe_ctx* ctx, const void* x_perm, const int32_t
     if (ctx->cfg.weight_format != MOE_W_MXFP4) return MOE_ERR_DTYPE;
     if (A == 0) return MOE_OK;
     if (!x_perm || !offsets || !w_gate_up || !s_gate_up || !w_down || !s_down || !y_perm) return MOE_ERR_NULL;
-    if (misaligned(x_perm) || misaligned(w_gate_up) || misaligned(w_down) || misaligned(y_perm)) return MOE_ERR_ALIGN;
+    if (misaligned(x_perm) || misaligned32(w_gate_up) || misaligned32(w_down) || misaligned(s_gate_up) ||
+        misaligned(s_down) || misaligned(y_perm))
+        return MOE_ERR_ALIGN;
     const moe_config& g = ctx->cfg;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    hipError_t e = launch_ffn_gate_up_w4(single_src(x_perm), nullptr, 1, offsets, A, g.E, g.H, g.I, w_gate_up, s_gate_up,
-                                         ctx->act, s);
+    hipError_t e = launch_ffn_gate_up_w4(ctx->ffn_variant, single_src(x_perm), nullptr, 1, offsets, A, g.E, g.H, g.I,
+                                         w_gate_up, s_gate_up, ctx->act, s);
     if (e != hipSuccess) return MOE_ERR_DEVICE;
-    return dev(launch_ffn_down_w4(ctx->act, offsets, A, g.E, g.H, g.I, w_down, s_down, y_perm, s));
+    return dev(launch_ffn_down_w4(ctx->ffn_variant, g.y_perm_f32 != 0, ctx->act, offsets, A, g.E, g.H, g.I, w_down,
+                                  s_down, y_perm, s));
 }
 
 moe_status moe_combine(moe_ctx* ctx, const void* y_perm, const int32_t* inv_perm, const float* topk_w,
@@ -341,8 +392,8 @@ moe_status moe_combine(moe_ctx* ctx, const void* y_perm, const int32_t* inv_perm
     if (!y_perm || !inv_perm || !topk_w || !y) return MOE_ERR_NULL;
     if (misaligned(y_perm) || misaligned(y) || (residual && misaligned(residual))) return MOE_ERR_ALIGN;
     const moe_config& g = ctx->cfg;
-    return dev(launch_combine(g.dtype, y_perm, inv_perm, topk_w, residual != nullptr, single_src(residual), T, g.K,
-                              g.H, y, T, y, static_cast<hipStream_t>(stream)));
+    return dev(launch_combine(g.dtype, g.y_perm_f32 != 0, y_perm, inv_perm, topk_w, residual != nullptr,
+                              single_src(residual), T, g.K, g.H, y, T, y, static_cast<hipStream_t>(stream)));
 }
 
 moe_status moe_group_forward(moe_ctx* ctx, const moe_layer* layers, int32_t n_layers, const void* x_decode,
@@ -464,7 +515,7 @@ moe_status moe_kernel_timing(moe_ctx* ctx, uint32_t kernel_mask)
 {
     if (!ctx) return MOE_ERR_NULL;
     if (kernel_mask >> MOE_KERNEL_COUNT) return MOE_ERR_SHAPE;
-    drop_timing(ctx);
+    drop_timing(ctx, false);
     ctx->timing_mask = kernel_mask;
     return MOE_OK;
 }
@@ -489,8 +540,16 @@ const char* moe_ffn_variant(const moe_ctx* ctx, int64_t T)
 {
     if (!ctx) return "";
     const moe_config& g = ctx->cfg;
-    if (g.weight_format == MOE_W_MXFP4) return ffn_w4_variant_name(T * g.K, g.E);
-    return ffn_variant_name(g.dtype, T * g.K, g.E, g.H, g.I);
+    if (g.weight_format == MOE_W_MXFP4) return ffn_w4_variant_name(ctx->ffn_variant, T * g.K, g.E);
+    return ffn_variant_name(g.dtype, ctx->ffn_variant, T * g.K, g.E, g.H, g.I);
+}
+
+moe_status moe_set_ffn_variant(moe_ctx* ctx, int32_t variant)
+{
+    if (!ctx) return MOE_ERR_NULL;
+    if (variant < MOE_FFN_AUTO || variant > MOE_FFN_W4_STREAM) return MOE_ERR_SHAPE;
+    ctx->ffn_variant = variant;
+    return MOE_OK;
 }
 
 const char* moe_status_string(moe_status s)
@@ -500,7 +559,7 @@ const char* moe_status_string(moe_status s)
         case MOE_ERR_NULL: return "null pointer";
         case MOE_ERR_SHAPE: return "bad shape or size";
         case MOE_ERR_DTYPE: return "unknown dtype";
-        case MOE_ERR_ALIGN: return "alignment (H, I multiples of 8; 16-byte aligned pointers)";
+        case MOE_ERR_ALIGN: return "alignment (H, I multiples of 8, 64 with MXFP4 weights; 16-byte aligned pointers, 32-byte for MXFP4 codes)";
         case MOE_ERR_WORKSPACE: return "workspace too small";
         case MOE_ERR_SCHEDULE: return "bad schedule";
         case MOE_ERR_DEVICE: return "HIP runtime error";

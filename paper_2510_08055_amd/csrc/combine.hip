@@ -36,12 +36,15 @@ template <> struct pack16<float> {
 
 // y rows [0, rows0) go to y0, rows [rows0, T) to y1 (row t - rows0): lets the layer-group driver
 // write decode rows and prefill rows to their separate output buffers without a copy.
-template <typename T>
-__global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ y_perm, const int32_t* __restrict__ inv,
+// YT: element type of y_perm (T, or float when the context keeps the expert outputs in fp32).
+template <typename T, typename YT>
+__global__ __launch_bounds__(256) void combine_kernel(const YT* __restrict__ y_perm, const int32_t* __restrict__ inv,
                                                       const float* __restrict__ w, bool has_residual,
                                                       RowSrc residual, int K, int H, T* y0, int64_t rows0, T* y1)
 {
     typedef pack16<T> P;
+    typedef pack16<YT> PY;
+    constexpr int NY = P::N / PY::N;      // 16-byte pieces of y_perm per 16 bytes of output (1, or 2 for fp32 under bf16)
     __shared__ int32_t s_row[kMaxTopK];
     __shared__ float s_w[kMaxTopK];
     const int64_t t = blockIdx.x;
@@ -56,9 +59,13 @@ __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ y_pe
 #pragma unroll
         for (int i = 0; i < P::N; ++i) acc[i] = 0.f;
         for (int j = 0; j < K; ++j) {
-            P p;
-            p.raw = *reinterpret_cast<const decltype(p.raw)*>(y_perm + (int64_t)s_row[j] * H + c);
-            p.unpack(v);
+            const YT* src = y_perm + (int64_t)s_row[j] * H + c;
+#pragma unroll
+            for (int h = 0; h < NY; ++h) {
+                PY p;
+                p.raw = *reinterpret_cast<const decltype(p.raw)*>(src + h * PY::N);
+                p.unpack(v + h * PY::N);
+            }
             const float wj = s_w[j];
 #pragma unroll
             for (int i = 0; i < P::N; ++i) acc[i] = fmaf(wj, v[i], acc[i]);
@@ -76,15 +83,19 @@ __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ y_pe
     }
 }
 
-hipError_t launch_combine(int dtype, const void* y_perm, const int32_t* inv, const float* w, bool has_residual,
-                          RowSrc residual, int64_t T, int K, int H, void* y0, int64_t rows0, void* y1, hipStream_t s)
+hipError_t launch_combine(int dtype, bool y_perm_f32, const void* y_perm, const int32_t* inv, const float* w,
+                          bool has_residual, RowSrc residual, int64_t T, int K, int H, void* y0, int64_t rows0, void* y1,
+                          hipStream_t s)
 {
-    if (dtype == MOE_BF16)
-        combine_kernel<bf16_t><<<(unsigned)T, 256, 0, s>>>((const bf16_t*)y_perm, inv, w, has_residual, residual, K,
-                                                           H, (bf16_t*)y0, rows0, (bf16_t*)y1);
+    if (dtype == MOE_BF16 && y_perm_f32)
+        combine_kernel<bf16_t, float><<<(unsigned)T, 256, 0, s>>>((const float*)y_perm, inv, w, has_residual, residual,
+                                                                  K, H, (bf16_t*)y0, rows0, (bf16_t*)y1);
+    else if (dtype == MOE_BF16)
+        combine_kernel<bf16_t, bf16_t><<<(unsigned)T, 256, 0, s>>>((const bf16_t*)y_perm, inv, w, has_residual, residual,
+                                                                   K, H, (bf16_t*)y0, rows0, (bf16_t*)y1);
     else
-        combine_kernel<float><<<(unsigned)T, 256, 0, s>>>((const float*)y_perm, inv, w, has_residual, residual, K, H,
-                                                          (float*)y0, rows0, (float*)y1);
+        combine_kernel<float, float><<<(unsigned)T, 256, 0, s>>>((const float*)y_perm, inv, w, has_residual, residual, K,
+                                                                 H, (float*)y0, rows0, (float*)y1);
     return hipGetLastError();
 }
 

@@ -62,6 +62,14 @@ hipError_t launch_router_logits(int dtype, RowSrc x, int64_t T, int H, const voi
 hipError_t launch_topk(const double* logits, int64_t T, int E, int K, int renorm, int32_t* idx, float* w,
                        int32_t* tile_hist, hipStream_t s);
 
+// The two-pass form of the two calls above (bf16 inputs, renormalised weights): a screening pass on the bf16
+// matrix cores, then exact fp64 logits for the experts that can be selected, top-k and weights.
+// cand_cnt [T] and cand [T, E] are scratch; zero_buf / tile_hist as above.
+bool router_two_pass_ok(int dtype, int renorm);
+hipError_t launch_router_two_pass(RowSrc x, int64_t T, int H, const void* w_router, const float* bias, int E, int K,
+                                  int32_t* cand_cnt, uint16_t* cand, int32_t* idx, float* w, int32_t* tile_hist,
+                                  int32_t* zero_buf, int zero_n, hipStream_t s);
+
 // permute.hip
 constexpr int kPermTile = 8192;  // assignments per block of the permutation kernels
 // hist_ready: tile_hist already holds the per-tile histograms (the top-k kernel counted them)
@@ -72,25 +80,44 @@ hipError_t launch_gather_rows(int dtype, const void* x, const int32_t* perm, int
                               void* x_perm, hipStream_t s);
 
 // combine.hip
-hipError_t launch_combine(int dtype, const void* y_perm, const int32_t* inv, const float* w, bool has_residual,
-                          RowSrc residual, int64_t T, int K, int H, void* y0, int64_t rows0, void* y1,
-                          hipStream_t s);
+// y_perm_f32: y_perm holds float whatever dtype is
+hipError_t launch_combine(int dtype, bool y_perm_f32, const void* y_perm, const int32_t* inv, const float* w,
+                          bool has_residual, RowSrc residual, int64_t T, int K, int H, void* y0, int64_t rows0,
+                          void* y1, hipStream_t s);
 
 // ffn.hip
 // x: [*, H]; row_map (or NULL): permuted row r reads x row row_map[r] / map_div; offsets [E+1].
-hipError_t launch_ffn_gate_up(int dtype, RowSrc x, const int32_t* row_map, int map_div,
+// variant: a moe_ffn_variant_id (MOE_FFN_AUTO: chosen from the mean rows per expert); out_f32: y_perm is float;
+// split: act is [A, 2I], every value a pair of bf16 (hi in column i, lo in column I + i); needs out_f32
+hipError_t launch_ffn_gate_up(int dtype, int variant, bool split, RowSrc x, const int32_t* row_map, int map_div,
                               const int32_t* offsets, int64_t A, int E, int H, int I, const void* w_gate_up,
                               void* act, hipStream_t s);
-hipError_t launch_ffn_down(int dtype, const void* act, const int32_t* offsets, int64_t A, int E, int H, int I,
-                           const void* w_down, void* y_perm, hipStream_t s);
-const char* ffn_variant_name(int dtype, int64_t A, int E, int H, int I);
+hipError_t launch_ffn_down(int dtype, int variant, bool out_f32, bool split, const void* act, const int32_t* offsets,
+                           int64_t A, int E, int H, int I, const void* w_down, void* y_perm, hipStream_t s);
+const char* ffn_variant_name(int dtype, int variant, int64_t A, int E, int H, int I);
+
+// Sets a kernel's dynamic-LDS limit once per device (the attribute belongs to the device's copy of the code
+// object).  `done` is the caller's per-kernel array of kMaxDevices flags.
+constexpr int kMaxDevices = 16;
+template <typename K> inline hipError_t ensure_lds_limit(K kern, size_t lds_bytes, bool* done)
+{
+    int d = 0;
+    hipError_t e = hipGetDevice(&d);
+    if (e != hipSuccess) return e;
+    if (d < 0 || d >= kMaxDevices) return hipErrorInvalidDevice;
+    if (done[d]) return hipSuccess;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)lds_bytes);
+    if (e == hipSuccess) done[d] = true;
+    return e;
+}
 
 // ffn_w4.hip: the same two GEMMs with MXFP4 expert weights (codes + scale bytes), bf16 activations
-hipError_t launch_ffn_gate_up_w4(RowSrc x, const int32_t* row_map, int map_div, const int32_t* offsets, int64_t A, int E,
-                                 int H, int I, const uint8_t* w_gate_up, const uint8_t* s_gate_up, void* act,
-                                 hipStream_t s);
-hipError_t launch_ffn_down_w4(const void* act, const int32_t* offsets, int64_t A, int E, int H, int I,
-                              const uint8_t* w_down, const uint8_t* s_down, void* y_perm, hipStream_t s);
-const char* ffn_w4_variant_name(int64_t A, int E);
+hipError_t launch_ffn_gate_up_w4(int variant, RowSrc x, const int32_t* row_map, int map_div, const int32_t* offsets,
+                                 int64_t A, int E, int H, int I, const uint8_t* w_gate_up, const uint8_t* s_gate_up,
+                                 void* act, hipStream_t s);
+hipError_t launch_ffn_down_w4(int variant, bool out_f32, const void* act, const int32_t* offsets, int64_t A, int E, int H,
+                              int I, const uint8_t* w_down, const uint8_t* s_down, void* y_perm, hipStream_t s);
+const char* ffn_w4_variant_name(int variant, int64_t A, int E);
 
 }  // namespace moe

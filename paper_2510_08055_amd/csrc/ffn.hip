@@ -5,9 +5,6 @@
 //
 // Both operands are K-contiguous (activations [rows,K], weights [N,K]), which is exactly
 // the MFMA operand layout: each lane feeds 8 consecutive k-values of one row.
-#include <stdlib.h>
-#include <string.h>
-
 #include "ffn_tile.h"
 
 namespace moe {
@@ -24,12 +21,16 @@ constexpr int kLdsStride = 72; // bf16 elements per LDS row: 64 + 8 pad -> 144 B
 // Global -> register -> LDS double buffering: the loads of stage s+1 are in flight while the
 // MFMAs of stage s run.
 // ----------------------------------------------------------------------------------------------
-template <int BM, int BN, bool GATED>
+// SPLIT (the intermediate held as a pair of bf16 values, value = hi + lo): the gated GEMM writes hi to
+// column n and lo = bf16(value - hi) to column N + n of its output; the plain GEMM reads such rows
+// (K = 2 * ldw k-values: the hi half, then the lo half) against weight rows of ldw values used twice.
+template <int BM, int BN, bool GATED, typename OT, bool SPLIT>
 __global__ __launch_bounds__(256) void grouped_gemm_bf16_kernel(
     RowSrc X, int ldx, const int32_t* __restrict__ row_map, int map_div,
     const int32_t* __restrict__ offsets, int E, const bf16_t* __restrict__ W, int64_t w_expert_stride, int N, int K,
-    bf16_t* __restrict__ Out, int ldo)
+    OT* __restrict__ Out, int ldo)
 {
+    const int ldw = (SPLIT && !GATED) ? K / 2 : K;      // k-values per weight row
     constexpr int NO = GATED ? BN / 2 : BN;          // output columns per block
     constexpr int TM = BM / 2 / 32;                  // 32-row MFMA tiles per wave
     constexpr int TNO = NO / 2 / 32;                 // 32-column output tiles per wave
@@ -71,7 +72,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16_kernel(
         else n = n0 + rb;
         if (n >= N) n = N - 1;
         if (GATED && rb >= NO) n += N;
-        b_src[p] = We + (int64_t)n * K + ld_chunk * 8;
+        b_src[p] = We + (int64_t)n * ldw + ld_chunk * 8;
     }
 
     float16_t acc[TM][TN];
@@ -88,9 +89,12 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16_kernel(
 #pragma unroll
         for (int p = 0; p < A_LOADS; ++p)
             a_reg[p] = in ? *reinterpret_cast<const uint4*>(a_src[p] + k0) : make_uint4(0, 0, 0, 0);
+        // second half of a split k-range: the same weight values again (ldw is a multiple of 8: a 16-byte
+        // chunk lies in one half)
+        const int kw = (k0 + ld_chunk * 8 >= ldw) ? k0 - ldw : k0;
 #pragma unroll
         for (int p = 0; p < B_LOADS; ++p)
-            b_reg[p] = in ? *reinterpret_cast<const uint4*>(b_src[p] + k0) : make_uint4(0, 0, 0, 0);
+            b_reg[p] = in ? *reinterpret_cast<const uint4*>(b_src[p] + kw) : make_uint4(0, 0, 0, 0);
     };
     auto store_stage = [&](int buf) {
 #pragma unroll
@@ -150,7 +154,12 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16_kernel(
                 float val;
                 if (GATED) val = silu_mul(acc[i][j][v], acc[i][j + TNO][v]);
                 else val = acc[i][j][v];
-                if (row < tc.row_end && col < N) Out[(int64_t)row * ldo + col] = f32_to_bf16(val);
+                if (SPLIT && GATED) val = opaque(val);
+                if (row < tc.row_end && col < N) {
+                    const OT hi = elem<OT>::from_f32(val);
+                    Out[(int64_t)row * ldo + col] = hi;
+                    if (SPLIT && GATED) Out[(int64_t)row * ldo + N + col] = elem<OT>::from_f32(val - elem<OT>::to_f32(hi));
+                }
             }
         }
     }
@@ -177,12 +186,16 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16_kernel(
 // The k-order of the MFMAs is the same as in the other variants (bit-identical results).
 // Requires K % PBK == 0.
 // ----------------------------------------------------------------------------------------------
-template <int RBM, int BN, int WM, int NSA, int NSB, int PBK, int MINW, int NW, int ORD, bool GATED>
+// OUT_F32: the output is stored as float (the down GEMM of a context that keeps y_perm in fp32).
+// SPLIT: the intermediate is a pair of bf16 values, as in the kernel above.
+template <int RBM, int BN, int WM, int NSA, int NSB, int PBK, int MINW, int NW, int ORD, bool GATED, bool OUT_F32,
+          bool SPLIT>
 __global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
     RowSrc X, int ldx, const int32_t* __restrict__ row_map, int map_div,
     const int32_t* __restrict__ offsets, int E, const bf16_t* __restrict__ W, int64_t w_expert_stride, int N, int K,
-    bf16_t* __restrict__ Out, int ldo, int a_rows)
+    void* __restrict__ Out_, int ldo, int a_rows)
 {
+    static_assert(!(GATED && OUT_F32), "the intermediate of the gated GEMM is always held in the activation dtype");
     constexpr int BM = RBM * 32, WN = NW / WM;   // NW waves arranged WM (rows) x WN (columns)
     constexpr int NO = GATED ? BN / 2 : BN;     // output columns per block
     constexpr int TM = RBM / WM;                // row blocks per wave: rb = wm + WM * i
@@ -236,6 +249,9 @@ __global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
     // and only then are the looked-up rows turned into activation addresses.
     const int l_row = lane / CPR, l_chunk = lane % CPR;
     const int nk_ = K / PBK;
+    // stages per weight row: with a split intermediate the plain GEMM walks every weight row twice
+    const int nk_w = (SPLIT && !GATED) ? nk_ / 2 : nk_;
+    const int ldw = (SPLIT && !GATED) ? K / 2 : K;
     // The lookups are loads issued from inline asm, picked up after an explicit wait further down: a
     // lookup through the compiler would be waited for with vmcnt(0) (it does not know of the asm-issued
     // weight loads that follow), i.e. together with the first weight stages out of HBM.  Until that wait
@@ -259,11 +275,12 @@ __global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
         else n = n0 + rb;
         if (n >= N) n = N - 1;
         if (GATED && rb >= NO) n += N;
-        b_src[p] = We + (int64_t)n * K + ((l_chunk ^ swz<PBK>(rb)) << 3);
+        b_src[p] = We + (int64_t)n * ldw + ((l_chunk ^ swz<PBK>(rb)) << 3);
     }
     const uint32_t lds0 = lds_address(smem);
     auto issue_b = [&](int kt, int p) {
-        load_lds_16(b_src[p] + kt * PBK, lds0 + B_BASE + (kt % NSB) * B_SLOT + (wave + NW * p) * 1024);
+        const int kw = (SPLIT && !GATED && kt >= nk_w) ? kt - nk_w : kt;
+        load_lds_16(b_src[p] + kw * PBK, lds0 + B_BASE + (kt % NSB) * B_SLOT + (wave + NW * p) * 1024);
     };
 #pragma unroll
     for (int st = 0; st < NSB - 1; ++st)
@@ -480,38 +497,84 @@ __global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
         constexpr int WPS = A_SLOT / REG;         // waves per free activation slot
         constexpr int RPI = 64 / CPRW;            // rows one wave-level 16-byte access covers
         static_assert(TNO <= 2 && WPS >= 1 && (NSA - 1) * WPS >= NW, "the epilogue staging does not fit the free slots");
-        if (TMV > 0) {
+        static_assert(!OUT_F32 || REG >= 4096, "a 32 x 32 float tile must fit the wave's staging piece");
+        if (TMV > 0 && OUT_F32) {
+            // float output: one 32 x 32 tile (4 KB: 32 rows of 8 16-byte chunks) at a time through the same
+            // private piece of LDS; a lane's 4 consecutive columns are one chunk, chunk c of row r sits in
+            // chunk slot c ^ (r & 7), and the tile goes out as 128-byte runs per row.
+            float* Out = static_cast<float*>(Out_);
             char* epi = smem + ((nk_ + wave / WPS) % NSA) * A_SLOT + (wave % WPS) * REG;
-            auto eswz = [](int r) { return (r >> (RB == 64 ? 2 : 1)) & (CPRW - 1); };
 #pragma unroll
             for (int i = 0; i < TMV; ++i) {
+                const int64_t row_base = (int64_t)tc.row0 + (wm + WM * i) * 32;
 #pragma unroll
                 for (int j = 0; j < TNO; ++j) {
 #pragma unroll
-                    for (int a = 0; a < 4; ++a) {
-                        float val[4];
+                    for (int a = 0; a < 4; ++a)
+                        *reinterpret_cast<float4*>(epi + fr * 128 + (((a * 2 + fq) ^ (fr & 7)) << 4)) =
+                            make_float4(acc[i][j][a * 4], acc[i][j][a * 4 + 1], acc[i][j][a * 4 + 2], acc[i][j][a * 4 + 3]);
+                    __builtin_amdgcn_wave_barrier();
 #pragma unroll
-                        for (int b = 0; b < 4; ++b) {
-                            if (GATED) val[b] = silu_mul(acc[i][j][a * 4 + b], acc[i][j + TNO][a * 4 + b]);
-                            else val[b] = acc[i][j][a * 4 + b];
-                        }
-                        const int chunk = (j * 4 + a) ^ eswz(fr);
-                        *reinterpret_cast<uint2*>(epi + fr * RB + chunk * 16 + fq * 8) =
-                            make_uint2(pack_bf16x2(val[0], val[1]), pack_bf16x2(val[2], val[3]));
+                    for (int h = 0; h < 4; ++h) {
+                        const int r = h * 8 + (lane >> 3), c = lane & 7;
+                        const float4 v = *reinterpret_cast<const float4*>(epi + r * 128 + ((c ^ (r & 7)) << 4));
+                        const int64_t row = row_base + r;
+                        const int col = n0 + wn * WNO + j * 32 + c * 4;
+                        if (row < tc.row_end && col < N)    // N is a multiple of 8: the 4 columns are in or out together
+                            *reinterpret_cast<float4*>(Out + row * ldo + col) = v;
                     }
+                    __builtin_amdgcn_wave_barrier();
                 }
-                __builtin_amdgcn_wave_barrier();
-                const int64_t row_base = (int64_t)tc.row0 + (wm + WM * i) * 32;
+            }
+        } else if (TMV > 0) {
+            bf16_t* Out = static_cast<bf16_t*>(Out_);
+            char* epi = smem + ((nk_ + wave / WPS) % NSA) * A_SLOT + (wave % WPS) * REG;
+            auto eswz = [](int r) { return (r >> (RB == 64 ? 2 : 1)) & (CPRW - 1); };
+            constexpr int PARTS = (SPLIT && GATED) ? 2 : 1;      // the values, then what their bf16 rounding left over
 #pragma unroll
-                for (int h = 0; h < 32 / RPI; ++h) {
-                    const int r = h * RPI + lane / CPRW, c = lane % CPRW;
-                    const uint4 v = *reinterpret_cast<const uint4*>(epi + r * RB + ((c ^ eswz(r)) * 16));
-                    const int64_t row = row_base + r;
-                    const int col = n0 + wn * WNO + c * 8;
-                    if (row < tc.row_end && col < N)    // N is a multiple of 8: a chunk is in or out as a whole
-                        *reinterpret_cast<uint4*>(Out + row * ldo + col) = v;
+            for (int i = 0; i < TMV; ++i) {
+                if (GATED) {
+#pragma unroll
+                    for (int j = 0; j < TNO; ++j)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) {
+                            acc[i][j][v] = silu_mul(acc[i][j][v], acc[i][j + TNO][v]);
+                            if (SPLIT) acc[i][j][v] = opaque(acc[i][j][v]);
+                        }
                 }
-                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int part = 0; part < PARTS; ++part) {
+#pragma unroll
+                    for (int j = 0; j < TNO; ++j) {
+#pragma unroll
+                        for (int a = 0; a < 4; ++a) {
+                            float val[4];
+#pragma unroll
+                            for (int b = 0; b < 4; ++b) val[b] = acc[i][j][a * 4 + b];
+                            const uint32_t p01 = pack_bf16x2(val[0], val[1]), p23 = pack_bf16x2(val[2], val[3]);
+                            if (PARTS == 2 && part == 0) {      // keep the remainders for the second part
+                                acc[i][j][a * 4 + 0] = val[0] - __uint_as_float(p01 << 16);
+                                acc[i][j][a * 4 + 1] = val[1] - __uint_as_float(p01 & 0xffff0000u);
+                                acc[i][j][a * 4 + 2] = val[2] - __uint_as_float(p23 << 16);
+                                acc[i][j][a * 4 + 3] = val[3] - __uint_as_float(p23 & 0xffff0000u);
+                            }
+                            const int chunk = (j * 4 + a) ^ eswz(fr);
+                            *reinterpret_cast<uint2*>(epi + fr * RB + chunk * 16 + fq * 8) = make_uint2(p01, p23);
+                        }
+                    }
+                    __builtin_amdgcn_wave_barrier();
+                    const int64_t row_base = (int64_t)tc.row0 + (wm + WM * i) * 32;
+#pragma unroll
+                    for (int h = 0; h < 32 / RPI; ++h) {
+                        const int r = h * RPI + lane / CPRW, c = lane % CPRW;
+                        const uint4 v = *reinterpret_cast<const uint4*>(epi + r * RB + ((c ^ eswz(r)) * 16));
+                        const int64_t row = row_base + r;
+                        const int col = n0 + wn * WNO + c * 8;
+                        if (row < tc.row_end && col < N)    // N is a multiple of 8: a chunk is in or out as a whole
+                            *reinterpret_cast<uint4*>(Out + row * ldo + part * N + col) = v;
+                    }
+                    __builtin_amdgcn_wave_barrier();
+                }
             }
         }
     };
@@ -571,62 +634,52 @@ __global__ __launch_bounds__(256) void grouped_gemm_f32_kernel(RowSrc X, int ldx
 // ----------------------------------------------------------------------------------------------
 enum Variant { V_TILE128 = 0, V_PIPE_SMALL, V_PIPE_BIG };
 
-static Variant pick_variant(int64_t A, int E, int K)
+static Variant pick_variant(int variant, int64_t A, int E, int K)
 {
-    static const char* force = getenv("MOE_FFN_VARIANT");   // tuning aid: "tile128", "small", "big"
     Variant v;
     const double mean_rows = (double)A / (double)E;
     if (mean_rows <= 64.0) v = V_PIPE_SMALL;   // weight streaming: 64 x 128 tiles, 3 stages of 64 k-values
     else v = V_PIPE_BIG;                       // up to 256-row tiles, 2 + 3 stages of 64 k-values
-    if (force) {
-        if (!strcmp(force, "tile128")) v = V_TILE128;
-        if (!strcmp(force, "small")) v = V_PIPE_SMALL;
-        if (!strcmp(force, "big")) v = V_PIPE_BIG;
-    }
+    if (variant == MOE_FFN_TILE128) v = V_TILE128;
+    if (variant == MOE_FFN_PIPE_SMALL) v = V_PIPE_SMALL;
+    if (variant == MOE_FFN_PIPE_BIG) v = V_PIPE_BIG;
     if (K % 64 != 0) v = V_TILE128;            // the pipelined kernels have no k-tail path
     return v;
 }
 
-template <int BM, int BN, bool GATED>
+template <int BM, int BN, bool GATED, typename OT, bool SPLIT>
 static hipError_t launch_tile(RowSrc X, int ldx, const int32_t* row_map, int map_div, const int32_t* offsets,
-                              int E, int64_t A, const bf16_t* W, int64_t w_expert_stride, int N, int K, bf16_t* Out,
+                              int E, int64_t A, const bf16_t* W, int64_t w_expert_stride, int N, int K, void* Out,
                               int ldo, hipStream_t s)
 {
     constexpr int NO = GATED ? BN / 2 : BN;
     const size_t lds_bytes = 2 * (size_t)(BM + BN) * kLdsStride * sizeof(bf16_t);
-    auto kern = grouped_gemm_bf16_kernel<BM, BN, GATED>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    auto kern = grouped_gemm_bf16_kernel<BM, BN, GATED, OT, SPLIT>;
+    static bool attr_set[kMaxDevices] = {};
+    hipError_t e = ensure_lds_limit(kern, lds_bytes, attr_set);
+    if (e != hipSuccess) return e;
     const int64_t n_tiles = (N + NO - 1) / NO;
     const int64_t m_tiles_max = (A + BM - 1) / BM + (A < E ? A : E);   // sum_e ceil(m_e / BM) never exceeds this
     const int64_t grid = ((m_tiles_max * n_tiles + 7) / 8) * 8;
     if (grid >= ((int64_t)1 << 31)) return hipErrorInvalidValue;   // the device-side tile search counts in 32 bits
-    kern<<<(unsigned)grid, 256, lds_bytes, s>>>(X, ldx, row_map, map_div, offsets, E, W, w_expert_stride, N, K, Out,
-                                                ldo);
+    kern<<<(unsigned)grid, 256, lds_bytes, s>>>(X, ldx, row_map, map_div, offsets, E, W, w_expert_stride, N, K,
+                                                static_cast<OT*>(Out), ldo);
     return hipGetLastError();
 }
 
-template <int RBM, int BN, int WM, int NSA, int NSB, int PBK, int MINW, int NW, int ORD, bool GATED>
+template <int RBM, int BN, int WM, int NSA, int NSB, int PBK, int MINW, int NW, int ORD, bool GATED, bool OUT_F32,
+          bool SPLIT>
 static hipError_t launch_pipe(RowSrc X, int ldx, const int32_t* row_map, int map_div, const int32_t* offsets,
-                              int E, int64_t A, const bf16_t* W, int64_t w_expert_stride, int N, int K, bf16_t* Out,
+                              int E, int64_t A, const bf16_t* W, int64_t w_expert_stride, int N, int K, void* Out,
                               int ldo, hipStream_t s)
 {
     constexpr int BM = RBM * 32;
     constexpr int NO = GATED ? BN / 2 : BN;
     const size_t lds_bytes = ((size_t)NSA * BM + (size_t)NSB * BN) * PBK * 2;
-    auto kern = grouped_gemm_bf16_pipe_kernel<RBM, BN, WM, NSA, NSB, PBK, MINW, NW, ORD, GATED>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    auto kern = grouped_gemm_bf16_pipe_kernel<RBM, BN, WM, NSA, NSB, PBK, MINW, NW, ORD, GATED, OUT_F32, SPLIT>;
+    static bool attr_set[kMaxDevices] = {};
+    hipError_t e = ensure_lds_limit(kern, lds_bytes, attr_set);
+    if (e != hipSuccess) return e;
     const int64_t n_tiles = (N + NO - 1) / NO;
     const int64_t m_tiles_max = (A + BM - 1) / BM + (A < E ? A : E);
     const int64_t grid = ((m_tiles_max * n_tiles + 7) / 8) * 8;
@@ -636,32 +689,41 @@ static hipError_t launch_pipe(RowSrc X, int ldx, const int32_t* row_map, int map
     return hipGetLastError();
 }
 
-template <bool GATED>
-static hipError_t launch_bf16(RowSrc X, int ldx, const int32_t* row_map, int map_div, const int32_t* offsets,
-                              int E, int64_t A, const bf16_t* W, int64_t w_expert_stride, int N, int K, bf16_t* Out,
-                              int ldo, hipStream_t s)
+// K: k-extent of the GEMM (twice the weight rows' length when the plain GEMM reads a split intermediate)
+template <bool GATED, bool OUT_F32, bool SPLIT>
+static hipError_t launch_bf16(int variant, RowSrc X, int ldx, const int32_t* row_map, int map_div,
+                              const int32_t* offsets, int E, int64_t A, const bf16_t* W, int64_t w_expert_stride,
+                              int N, int K, void* Out, int ldo, hipStream_t s)
 {
     // weight streaming: 64 x 128 tiles, 4 waves, 72 KB of LDS: two blocks share a compute unit, so one
     // block's prologue and epilogue are covered by the other's loads, and the many small tiles balance
     // well over the chip.  compute bound: 256 x 256 tiles, 8 waves (2 per SIMD: one wave's barrier and
     // LDS waits are covered by the other's MFMAs), 2 (rows) x 4 (columns).
-    switch (pick_variant(A, E, K)) {
+    switch (pick_variant(variant, A, E, (SPLIT && !GATED) ? K / 2 : K)) {
         case V_PIPE_SMALL:
-            return launch_pipe<2, 128, 2, 3, 3, 64, 2, 4, 0, GATED>(X, ldx, row_map, map_div, offsets, E, A, W, w_expert_stride, N, K, Out, ldo, s);
+            return launch_pipe<2, 128, 2, 3, 3, 64, 2, 4, 0, GATED, OUT_F32, SPLIT>(X, ldx, row_map, map_div, offsets, E, A, W, w_expert_stride, N, K, Out, ldo, s);
         case V_PIPE_BIG:
-            return launch_pipe<8, 256, 2, 2, 3, 64, 2, 8, 3, GATED>(X, ldx, row_map, map_div, offsets, E, A, W, w_expert_stride, N, K, Out, ldo, s);
+            return launch_pipe<8, 256, 2, 2, 3, 64, 2, 8, 3, GATED, OUT_F32, SPLIT>(X, ldx, row_map, map_div, offsets, E, A, W, w_expert_stride, N, K, Out, ldo, s);
         default:
-            return launch_tile<128, 128, GATED>(X, ldx, row_map, map_div, offsets, E, A, W, w_expert_stride, N, K, Out,
-                                                ldo, s);
+            if (OUT_F32)
+                return launch_tile<128, 128, GATED, float, SPLIT>(X, ldx, row_map, map_div, offsets, E, A, W,
+                                                                  w_expert_stride, N, K, Out, ldo, s);
+            return launch_tile<128, 128, GATED, bf16_t, SPLIT>(X, ldx, row_map, map_div, offsets, E, A, W,
+                                                               w_expert_stride, N, K, Out, ldo, s);
     }
 }
 
-hipError_t launch_ffn_gate_up(int dtype, RowSrc x, const int32_t* row_map, int map_div, const int32_t* offsets,
-                              int64_t A, int E, int H, int I, const void* w_gate_up, void* act, hipStream_t s)
+hipError_t launch_ffn_gate_up(int dtype, int variant, bool split, RowSrc x, const int32_t* row_map, int map_div,
+                              const int32_t* offsets, int64_t A, int E, int H, int I, const void* w_gate_up, void* act,
+                              hipStream_t s)
 {
-    if (dtype == MOE_BF16)
-        return launch_bf16<true>(x, H, row_map, map_div, offsets, E, A, (const bf16_t*)w_gate_up,
-                                 (int64_t)2 * I * H, I, H, (bf16_t*)act, I, s);
+    if (dtype == MOE_BF16) {
+        if (split)      // act [A, 2I]: the values' bf16 roundings in columns [0, I), the remainders in [I, 2I)
+            return launch_bf16<true, false, true>(variant, x, H, row_map, map_div, offsets, E, A, (const bf16_t*)w_gate_up,
+                                                  (int64_t)2 * I * H, I, H, act, 2 * I, s);
+        return launch_bf16<true, false, false>(variant, x, H, row_map, map_div, offsets, E, A, (const bf16_t*)w_gate_up,
+                                               (int64_t)2 * I * H, I, H, act, I, s);
+    }
     const unsigned grid = (unsigned)((A * I + 255) / 256);
     grouped_gemm_f32_kernel<true><<<grid, 256, 0, s>>>(x, H, row_map, map_div, offsets, E,
                                                        (const float*)w_gate_up, (int64_t)2 * I * H, I, H, A,
@@ -669,12 +731,19 @@ hipError_t launch_ffn_gate_up(int dtype, RowSrc x, const int32_t* row_map, int m
     return hipGetLastError();
 }
 
-hipError_t launch_ffn_down(int dtype, const void* act, const int32_t* offsets, int64_t A, int E, int H, int I,
-                           const void* w_down, void* y_perm, hipStream_t s)
+hipError_t launch_ffn_down(int dtype, int variant, bool out_f32, bool split, const void* act, const int32_t* offsets,
+                           int64_t A, int E, int H, int I, const void* w_down, void* y_perm, hipStream_t s)
 {
-    if (dtype == MOE_BF16)
-        return launch_bf16<false>(single_src(act), I, nullptr, 1, offsets, E, A, (const bf16_t*)w_down,
-                                  (int64_t)H * I, H, I, (bf16_t*)y_perm, H, s);
+    if (dtype == MOE_BF16) {
+        if (split)      // (a split intermediate comes with fp32 expert outputs)
+            return launch_bf16<false, true, true>(variant, single_src(act), 2 * I, nullptr, 1, offsets, E, A,
+                                                  (const bf16_t*)w_down, (int64_t)H * I, H, 2 * I, y_perm, H, s);
+        if (out_f32)
+            return launch_bf16<false, true, false>(variant, single_src(act), I, nullptr, 1, offsets, E, A,
+                                                   (const bf16_t*)w_down, (int64_t)H * I, H, I, y_perm, H, s);
+        return launch_bf16<false, false, false>(variant, single_src(act), I, nullptr, 1, offsets, E, A,
+                                                (const bf16_t*)w_down, (int64_t)H * I, H, I, y_perm, H, s);
+    }
     const unsigned grid = (unsigned)((A * H + 255) / 256);
     grouped_gemm_f32_kernel<false><<<grid, 256, 0, s>>>(single_src(act), I, nullptr, 1, offsets, E,
                                                         (const float*)w_down, (int64_t)H * I, H, I, A,
@@ -682,11 +751,11 @@ hipError_t launch_ffn_down(int dtype, const void* act, const int32_t* offsets, i
     return hipGetLastError();
 }
 
-const char* ffn_variant_name(int dtype, int64_t A, int E, int H, int I)
+const char* ffn_variant_name(int dtype, int variant, int64_t A, int E, int H, int I)
 {
     (void)I;
     if (dtype != MOE_BF16) return "grouped_gemm_f32_kernel<gated>";
-    switch (pick_variant(A, E, H)) {
+    switch (pick_variant(variant, A, E, H)) {
         case V_PIPE_SMALL: return "grouped_gemm_bf16_pipe_kernel<2,128,2,3,3,64,2,4,0,gated>";
         case V_PIPE_BIG: return "grouped_gemm_bf16_pipe_kernel<8,256,2,2,3,64,2,8,3,gated>";
         default: return "grouped_gemm_bf16_kernel<128,128,gated>";

@@ -114,6 +114,14 @@ __device__ __forceinline__ float silu_mul(float g, float u)
     return g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * u;
 }
 
+// The value as it stands in a register: the compiler can no longer fuse the multiplication that produced it
+// into a later subtraction (fp contraction would make `v - round(v)` depend on where it is compiled).
+__device__ __forceinline__ float opaque(float v)
+{
+    asm volatile("" : "+v"(v));
+    return v;
+}
+
 typedef __attribute__((address_space(3))) void lds_ptr_t;
 typedef __attribute__((address_space(1))) const void glb_ptr_t;
 

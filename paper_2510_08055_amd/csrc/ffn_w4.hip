@@ -19,9 +19,6 @@
 // values each, and the activation fragments follow the same k assignment; stages and MFMAs run in the
 // same ascending order, so the two shapes produce bit-identical results and a chunked and a layered pass
 // may pick different ones.
-#include <cstdlib>
-#include <cstring>
-
 #include "ffn_tile.h"
 
 namespace moe {
@@ -90,12 +87,14 @@ template <int SH> __device__ __forceinline__ float e8m0_byte_to_float(uint32_t w
 //   Out[r, n] = silu(sum_k X.. * W[e, n, k]) * (sum_k X.. * W[e, N + n, k])            (GATED = true)
 // W: packed codes [E][rows][K/2] bytes, S: scales [E][rows][K/32] bytes; rows = N (or 2N when GATED).
 // Requires K % 64 == 0.
-template <bool GATED>
+// OUT_F32: the output is stored as float (down GEMM of a context that keeps y_perm in fp32).
+template <bool GATED, bool OUT_F32>
 __global__ __launch_bounds__(kW4Waves * 64, 2) void grouped_gemm_w4_kernel(
     RowSrc X, int ldx, const int32_t* __restrict__ row_map, int map_div, const int32_t* __restrict__ offsets, int E,
     const uint8_t* __restrict__ W, const uint8_t* __restrict__ S, int64_t rows_per_expert, int N, int K,
-    bf16_t* __restrict__ Out, int ldo, int a_rows)
+    void* __restrict__ Out_, int ldo, int a_rows)
 {
+    static_assert(!(GATED && OUT_F32), "the intermediate of the gated GEMM is always bf16");
     constexpr int BM = kW4Rows, BN = kW4BN, NW = kW4Waves, NSA = kW4NSA, NSB = kW4NSB, PBK = kW4K;
     constexpr int WN = NW;                      // the waves sit side by side along the weight rows
     constexpr int TM = BM / 32;                 // every wave multiplies all row blocks of the tile
@@ -338,9 +337,14 @@ __global__ __launch_bounds__(kW4Waves * 64, 2) void grouped_gemm_w4_kernel(
                     if (GATED) val[b] = silu_mul(acc[i][j][a * 4 + b], acc[i][j + TNO][a * 4 + b]);
                     else val[b] = acc[i][j][a * 4 + b];
                 }
-                if (row < tc.row_end && col < N)    // N is a multiple of 8: the 4 columns are in or out together
-                    *reinterpret_cast<uint2*>(Out + row * ldo + col) =
-                        make_uint2(pack_bf16x2(val[0], val[1]), pack_bf16x2(val[2], val[3]));
+                if (row < tc.row_end && col < N) {  // N is a multiple of 8: the 4 columns are in or out together
+                    if (OUT_F32)
+                        *reinterpret_cast<float4*>(static_cast<float*>(Out_) + row * ldo + col) =
+                            make_float4(val[0], val[1], val[2], val[3]);
+                    else
+                        *reinterpret_cast<uint2*>(static_cast<bf16_t*>(Out_) + row * ldo + col) =
+                            make_uint2(pack_bf16x2(val[0], val[1]), pack_bf16x2(val[2], val[3]));
+                }
             }
         }
     }
@@ -394,12 +398,13 @@ __device__ __forceinline__ void settle(u32x4_t& v) { asm volatile("" : "+v"(v)::
 
 // ODD: the row bytes are an odd multiple of 32 (the four line loads of a wave have the four classes).
 // (second launch bound: waves per SIMD; two blocks of 8 waves per compute unit = 4)
-template <bool GATED, bool ODD>
+template <bool GATED, bool ODD, bool OUT_F32>
 __global__ __launch_bounds__(kS4Waves * 64, 4) void grouped_gemm_w4_stream_kernel(
     RowSrc X, int ldx, const int32_t* __restrict__ row_map, int map_div, const int32_t* __restrict__ offsets, int E,
     const uint8_t* __restrict__ W, const uint8_t* __restrict__ S, int64_t rows_per_expert, int N, int K,
-    bf16_t* __restrict__ Out, int ldo, int a_rows)
+    void* __restrict__ Out_, int ldo, int a_rows)
 {
+    static_assert(!(GATED && OUT_F32), "the intermediate of the gated GEMM is always bf16");
     constexpr int BM = kS4Rows, BN = kW4BN, NW = kS4Waves, NSA = kS4NSA, PBK = kW4K;
     constexpr int NO = GATED ? BN / 2 : BN;     // output columns per block
     constexpr int A_ROWB = PBK * 2, A_SLOT = BM * A_ROWB;        // 128-byte activation rows, 4 KB per stage
@@ -429,14 +434,18 @@ __global__ __launch_bounds__(kS4Waves * 64, 4) void grouped_gemm_w4_stream_kerne
     const int a_lrow = lane >> 3, a_chunk = lane & 7;
     const int tile_rows = tc.row_end - tc.row0;     // 1 .. 32
     const bool a_loader = wave * 8 < tile_rows;     // (false for waves 4..7); a load whose rows all lie past the tile's last row is left out
-    int32_t a_row_id;
+    int32_t a_row_id, a_own;
     {
         int r = tc.row0 + wave * 8 + a_lrow;
         if (r >= tc.row_end) r = tc.row_end - 1;
-        a_row_id = r;
+        a_own = r;
         // fetched without a compiler-tracked wait: the weight loads below go out while it is in flight, and
-        // the explicit wait in front of its first use leaves exactly those outstanding
-        if (row_map) asm volatile("global_load_dword %0, %1, off" : "=v"(a_row_id) : "v"(row_map + r) : "memory");
+        // the explicit wait in front of its first use leaves exactly those outstanding.  The load is issued
+        // in every case (without a row map it reads a valid dummy word, offsets[0], and the result is
+        // ignored): a conditional load would be an asm output merged with an earlier value, i.e. a register
+        // copy that the compiler may place behind the load.
+        const int32_t* src = row_map ? row_map + r : offsets;
+        asm volatile("global_load_dword %0, %1, off" : "=v"(a_row_id) : "v"(src) : "memory");
     }
 
     // Tile row t -> row of the expert's weight matrix.  A row past the matrix (ragged last n-tile) is
@@ -598,9 +607,10 @@ __global__ __launch_bounds__(kS4Waves * 64, 4) void grouped_gemm_w4_stream_kerne
         // down to this lane's bytes
         wait_vmcnt<B_LPW>();
         asm volatile("" : "+v"(a_row_id)::"memory");
-        if (row_map) {      // a row map holds indices below a_rows; the clamp keeps a bad entry from becoming a wild address
-            a_row_id = a_row_id < 0 ? 0 : a_row_id;
-            a_row_id = a_row_id < a_rows ? a_row_id : a_rows - 1;
+        {      // a row map holds indices below a_rows; the clamp keeps a bad entry from becoming a wild address
+            int32_t id = a_row_id < 0 ? 0 : a_row_id;
+            id = id < a_rows ? id : a_rows - 1;
+            a_row_id = row_map ? id : a_own;
         }
 #pragma unroll
         for (int i = 0; i < 8; ++i) keep_piece(s_raw[i], i < s_row_pieces ? i : s_row_pieces - 1, s_lo[i], s_hi[i]);
@@ -746,9 +756,14 @@ __global__ __launch_bounds__(kS4Waves * 64, 4) void grouped_gemm_w4_stream_kerne
 #pragma unroll
             for (int b = 0; b < 4; ++b) val[b] = acc[a * 4 + b];
         }
-        if (row < tc.row_end && col < N)    // N is a multiple of 8: the 4 columns are in or out together
-            *reinterpret_cast<uint2*>(Out + row * ldo + col) =
-                make_uint2(pack_bf16x2(val[0], val[1]), pack_bf16x2(val[2], val[3]));
+        if (row < tc.row_end && col < N) {  // N is a multiple of 8: the 4 columns are in or out together
+            if (OUT_F32)
+                *reinterpret_cast<float4*>(static_cast<float*>(Out_) + row * ldo + col) =
+                    make_float4(val[0], val[1], val[2], val[3]);
+            else
+                *reinterpret_cast<uint2*>(static_cast<bf16_t*>(Out_) + row * ldo + col) =
+                    make_uint2(pack_bf16x2(val[0], val[1]), pack_bf16x2(val[2], val[3]));
+        }
     }
 }
 
@@ -756,36 +771,34 @@ __global__ __launch_bounds__(kS4Waves * 64, 4) void grouped_gemm_w4_stream_kerne
 // 32-row tiles re-read (from L2) and re-widen the weights once per 32 rows, which a prefill-heavy batch
 // pays for: measured on 32 experts x 5760 x 2880 the two shapes are level at 40 rows per expert, the
 // streaming shape 3 % ahead at 72, 5 % behind at 136 and 13 % behind at 264.
-bool w4_use_stream(int64_t A, int E)
+bool w4_use_stream(int variant, int64_t A, int E)
 {
-    const char* force = getenv("MOE_FFN_VARIANT");    // tuning and test aid: "w4_tile64", "w4_stream"
-    if (force && !strcmp(force, "w4_tile64")) return false;
-    if (force && !strcmp(force, "w4_stream")) return true;
+    if (variant == MOE_FFN_W4_TILE64) return false;
+    if (variant == MOE_FFN_W4_STREAM) return true;
     return A <= (int64_t)96 * E;
 }
 
-template <bool GATED>
-hipError_t launch_w4(RowSrc X, int ldx, const int32_t* row_map, int map_div, const int32_t* offsets, int E, int64_t A,
-                     const uint8_t* W, const uint8_t* S, int64_t rows_per_expert, int N, int K, bf16_t* Out, int ldo,
-                     hipStream_t s)
+template <bool GATED, bool OUT_F32>
+hipError_t launch_w4(int variant, RowSrc X, int ldx, const int32_t* row_map, int map_div, const int32_t* offsets, int E,
+                     int64_t A, const uint8_t* W, const uint8_t* S, int64_t rows_per_expert, int N, int K, void* Out,
+                     int ldo, hipStream_t s)
 {
     constexpr int NO = GATED ? kW4BN / 2 : kW4BN;
-    const bool stream = w4_use_stream(A, E);
+    // the streaming kernel takes a row's address mod 128 for a multiple of 32 (the callers check it)
+    if ((reinterpret_cast<uintptr_t>(W) & 31u) != 0) return hipErrorInvalidValue;
+    const bool stream = w4_use_stream(variant, A, E);
     const int tile_rows = stream ? kS4Rows : kW4Rows;
     const size_t lds_bytes = stream ? (size_t)kS4NSA * kS4Rows * kW4K * 2 + (size_t)2 * kW4BN * 128
                                     : (size_t)kW4NSA * kW4Rows * kW4K * 2 + (size_t)kW4NSB * kW4BN * kW4K +
                                           2 * kW4BN * 16;   // scale area: max(3 dword slots, 2 chunk slots)
     const bool odd = ((K / 2) >> 5) & 1;     // row bytes an odd multiple of 32
-    auto kern = stream ? (odd ? grouped_gemm_w4_stream_kernel<GATED, true> : grouped_gemm_w4_stream_kernel<GATED, false>)
-                       : grouped_gemm_w4_kernel<GATED>;
-    static bool attr_set[3] = {false, false, false};
+    auto kern = stream ? (odd ? grouped_gemm_w4_stream_kernel<GATED, true, OUT_F32>
+                              : grouped_gemm_w4_stream_kernel<GATED, false, OUT_F32>)
+                       : grouped_gemm_w4_kernel<GATED, OUT_F32>;
+    static bool attr_set[3][kMaxDevices] = {};
     const int which = stream ? (odd ? 2 : 1) : 0;
-    if (!attr_set[which]) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-        if (e != hipSuccess) return e;
-        attr_set[which] = true;
-    }
+    hipError_t e = ensure_lds_limit(kern, lds_bytes, attr_set[which]);
+    if (e != hipSuccess) return e;
     const int64_t n_tiles = (N + NO - 1) / NO;
     const int64_t m_tiles_max = (A + tile_rows - 1) / tile_rows + (A < E ? A : E);
     const int64_t grid = ((m_tiles_max * n_tiles + 7) / 8) * 8;
@@ -797,24 +810,27 @@ hipError_t launch_w4(RowSrc X, int ldx, const int32_t* row_map, int map_div, con
 
 }  // namespace
 
-hipError_t launch_ffn_gate_up_w4(RowSrc x, const int32_t* row_map, int map_div, const int32_t* offsets, int64_t A, int E,
-                                 int H, int I, const uint8_t* w_gate_up, const uint8_t* s_gate_up, void* act,
-                                 hipStream_t s)
+hipError_t launch_ffn_gate_up_w4(int variant, RowSrc x, const int32_t* row_map, int map_div, const int32_t* offsets,
+                                 int64_t A, int E, int H, int I, const uint8_t* w_gate_up, const uint8_t* s_gate_up,
+                                 void* act, hipStream_t s)
 {
-    return launch_w4<true>(x, H, row_map, map_div, offsets, E, A, w_gate_up, s_gate_up, (int64_t)2 * I, I, H,
-                           (bf16_t*)act, I, s);
+    return launch_w4<true, false>(variant, x, H, row_map, map_div, offsets, E, A, w_gate_up, s_gate_up, (int64_t)2 * I, I,
+                                  H, act, I, s);
 }
 
-hipError_t launch_ffn_down_w4(const void* act, const int32_t* offsets, int64_t A, int E, int H, int I,
-                              const uint8_t* w_down, const uint8_t* s_down, void* y_perm, hipStream_t s)
+hipError_t launch_ffn_down_w4(int variant, bool out_f32, const void* act, const int32_t* offsets, int64_t A, int E, int H,
+                              int I, const uint8_t* w_down, const uint8_t* s_down, void* y_perm, hipStream_t s)
 {
-    return launch_w4<false>(single_src(act), I, nullptr, 1, offsets, E, A, w_down, s_down, (int64_t)H, H, I,
-                            (bf16_t*)y_perm, H, s);
+    if (out_f32)
+        return launch_w4<false, true>(variant, single_src(act), I, nullptr, 1, offsets, E, A, w_down, s_down, (int64_t)H, H,
+                                      I, y_perm, H, s);
+    return launch_w4<false, false>(variant, single_src(act), I, nullptr, 1, offsets, E, A, w_down, s_down, (int64_t)H, H, I,
+                                   y_perm, H, s);
 }
 
-const char* ffn_w4_variant_name(int64_t A, int E)
+const char* ffn_w4_variant_name(int variant, int64_t A, int E)
 {
-    return w4_use_stream(A, E) ? "grouped_gemm_w4_stream_kernel<gated>" : "grouped_gemm_w4_kernel<gated>";
+    return w4_use_stream(variant, A, E) ? "grouped_gemm_w4_stream_kernel<gated>" : "grouped_gemm_w4_kernel<gated>";
 }
 
 }  // namespace moe

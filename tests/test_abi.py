@@ -31,9 +31,9 @@ def test_status_strings():
     assert len({binding.status_string(i) for i in range(8)}) == 8
 
 
-def _ws(H=256, E=8, K=2, I=512, dtype=1, T=64, wfmt=0):
+def _ws(H=256, E=8, K=2, I=512, dtype=1, T=64, wfmt=0, yf32=0, split=0):
     lib = binding.load()
-    cfg = binding.CConfig(H, E, K, I, dtype, 1, 1, wfmt)
+    cfg = binding.CConfig(H, E, K, I, dtype, 1, 1, wfmt, yf32, split)
     n = ctypes.c_size_t(0)
     return lib.moe_workspace_bytes(ctypes.byref(cfg), T, ctypes.byref(n)), n.value
 
@@ -57,6 +57,12 @@ def test_workspace_bytes_and_argument_errors():
     assert _ws(wfmt=1, dtype=0)[0] == 3
     assert _ws(wfmt=1, H=96)[0] == 4 and _ws(wfmt=1, I=96)[0] == 4
     assert _ws(wfmt=2)[0] == 3
+    # fp32 expert outputs and a split intermediate: more workspace; the split needs bf16 weights and fp32 outputs
+    st3, n3 = _ws(yf32=1)
+    st4, n4 = _ws(yf32=1, split=1)
+    assert st3 == 0 and st4 == 0 and n3 >= n + 64 * 2 * 256 * 2 and n4 >= n3 + 64 * 2 * 512 * 2
+    assert _ws(yf32=2)[0] == 3 and _ws(yf32=1, split=2)[0] == 3
+    assert _ws(split=1)[0] == 3 and _ws(yf32=1, split=1, dtype=0)[0] == 3 and _ws(yf32=1, split=1, wfmt=1)[0] == 3
     lib = binding.load()
     assert lib.moe_workspace_bytes(None, 64, ctypes.byref(ctypes.c_size_t(0))) == 1   # MOE_ERR_NULL
     cfg = binding.CConfig(256, 8, 2, 512, 1, 1, 1)
@@ -75,6 +81,7 @@ def test_create_rejects_bad_arguments_before_touching_the_gpu():
     assert lib.moe_create(ctypes.byref(bad), 64, fake, 1 << 30, None, ctypes.byref(ctx)) == 2
     assert lib.moe_destroy(None) == 1
     assert lib.moe_router_topk(None, None, 4, None, None, None, None, None) == 1
+    assert lib.moe_set_ffn_variant(None, 0) == 1
 
 
 def test_group_count_rule_and_layer_groups_are_host_arithmetic():

@@ -253,31 +253,94 @@ def test_group_forward_edge_cases(gpu_lib):
     small.moe_group_forward(layers, xd, xp, "chunked", 16)        # fits: 9 + 16 rows per iteration
 
 
-# --------------------------------------------------- full benchmark shape, sampled outputs
-def test_qwen3_layer_full_size_sampled(gpu_lib):
-    w = inputs.WORKLOADS["qwen3_layer"]
-    L = inputs.make_layer(w, 0, device=DEV)
-    xd, xp = inputs.make_hidden(w, device=DEV)
-    T = w.D + w.P
-    ctx = make_ctx(gpu_lib, w, T)
-    yd, yp = ctx.moe_group_forward([L], xd, xp, "layered")
-    y = torch.cat([yd, yp])
-    x = torch.cat([xd, xp])
-    idx, wt = ctx.moe_router_topk(x, L["w_router"])
-    counts, offsets, perm, inv, _ = ctx.moe_permute(x, idx, want_x_perm=False)
-    Ln = inputs.layer_to_numpy(L)
-    xn = inputs.to_numpy(x)
-    o_idx, o_w, gap = oracle.router_topk(xn, Ln["w_router"], None, w.K, want_gap=True)     # all tokens
-    assert gap.min() > 1e-9
-    assert (idx.cpu().numpy() == o_idx).all()
-    np.testing.assert_allclose(wt.cpu().numpy(), o_w, rtol=2e-6, atol=1e-9)
-    oc, oo, op, oi = oracle.permute(o_idx, w.E)
-    assert (counts.cpu().numpy() == oc).all() and (offsets.cpu().numpy() == oo).all()
-    assert (perm.cpu().numpy() == op).all() and (inv.cpu().numpy() == oi).all()
-    assert oc.sum() == T * w.K and abs(oc.mean() - T * w.K / w.E) < 1e-9
-    rows = np.unique(np.concatenate([np.arange(4), np.random.default_rng(0).choice(T, 44, replace=False), [T - 1]]))
-    o_y, _, _ = oracle.moe_layer(xn[rows], Ln["w_router"], None, Ln["w_gate_up"], Ln["w_down"], w.K)
-    assert_close(y[torch.from_numpy(rows).to(DEV)], o_y, "bf16", "qwen3 layer (sampled rows)")
-    # schedule equivalence at full size: chunked(512) routes and computes the same rows
-    yd_c, yp_c = ctx.moe_group_forward([L], xd, xp, "chunked", w.chunk)
-    assert torch.equal(yd_c, yd) and torch.equal(yp_c, yp)
+# ------------------------------------------------ output-side formats and kernel shapes
+FORMATS = [dict(), dict(y_perm_f32=True), dict(y_perm_f32=True, act_split=True)]
+FORMAT_LAYERS = [
+    SMALL_LAYERS[0], SMALL_LAYERS[2],
+    inputs.Workload("s_tail", H=192, E=4, K=2, I=72, n_layers=1, D=7, P=290, dtype="bf16", seed=35, residual=False),   # k tails: tile kernel only
+    inputs.Workload("s_wide", H=128, E=2, K=1, I=1216, n_layers=1, D=0, P=330, dtype="bf16", seed=36, residual=True),   # 19 + 19 k-stages in the down GEMM
+]
+
+
+@pytest.mark.parametrize("fmt", range(len(FORMATS)), ids=["bf16", "y_perm_f32", "act_split"])
+@pytest.mark.parametrize("w", FORMAT_LAYERS, ids=lambda w: w.name)
+def test_output_side_formats_on_every_kernel_shape(gpu_lib, w, fmt):
+    """Expert outputs in fp32 and the intermediate as a bf16 pair: every grouped-GEMM shape gives the same bits,
+    the step calls equal the fused driver, and the result stays within tolerance of the oracle (closer to it
+    the more is kept: checked on the relative L2 error)."""
+    L = inputs.make_layer(w, 0)
+    Ld, Ln = dev_layer(L), inputs.layer_to_numpy(L)
+    xd, xp = inputs.make_hidden(w)
+    x = torch.cat([xd, xp]).to(DEV)
+    o_y, _, _ = oracle.moe_layer(inputs.to_numpy(x), Ln["w_router"], None, Ln["w_gate_up"], Ln["w_down"], w.K,
+                                 residual=w.residual)
+    ctx = gpu_lib.Context(w.H, w.E, w.K, w.I, torch.bfloat16, max_tokens=w.D + w.P, residual=w.residual, device=DEV,
+                          **FORMATS[fmt])
+    outs = {}
+    for variant in ("tile128", "small", "big", "auto"):
+        ctx.moe_set_ffn_variant(variant)
+        idx, wt = ctx.moe_router_topk(x, Ld["w_router"])
+        _, offsets, _, inv, x_perm = ctx.moe_permute(x, idx)
+        y_perm = ctx.moe_grouped_ffn(x_perm, offsets, Ld["w_gate_up"], Ld["w_down"])
+        assert y_perm.dtype == (torch.float32 if fmt else torch.bfloat16)
+        y = ctx.moe_combine(y_perm, inv, wt, residual=x if w.residual else None)
+        yd, yp = ctx.moe_group_forward([Ld], x[:w.D] if w.D else None, x[w.D:], "layered")
+        assert torch.equal(torch.cat([t for t in (yd, yp) if t.shape[0]]), y), variant
+        yd, yp = ctx.moe_group_forward([Ld], x[:w.D] if w.D else None, x[w.D:], "chunked", 100)
+        assert torch.equal(torch.cat([t for t in (yd, yp) if t.shape[0]]), y), variant
+        outs[variant] = y
+    for variant in ("small", "big", "auto"):
+        assert torch.equal(outs[variant], outs["tile128"]), variant
+    st = assert_close(outs["auto"], o_y, "bf16", f"{w.name} {FORMATS[fmt]}")
+    # what each format is for: the error that is left
+    base = gpu_lib.Context(w.H, w.E, w.K, w.I, torch.bfloat16, max_tokens=w.D + w.P, residual=w.residual, device=DEV)
+    yd, yp = base.moe_group_forward([Ld], x[:w.D] if w.D else None, x[w.D:], "layered")
+    st0 = assert_close(torch.cat([t for t in (yd, yp) if t.shape[0]]), o_y, "bf16", w.name)
+    if fmt:
+        assert st["rel_l2"] < st0["rel_l2"]
+
+
+def test_config_rejects_bad_output_side_formats(gpu_lib):
+    for kw in (dict(act_split=True), dict(y_perm_f32=True, act_split=True, weight_format="mxfp4")):
+        with pytest.raises(gpu_lib.MoeError) as e:
+            gpu_lib.Context(128, 4, 2, 64, torch.bfloat16, max_tokens=8, device=DEV, **kw)
+        assert e.value.status == 3
+    with pytest.raises(gpu_lib.MoeError) as e:
+        gpu_lib.Context(128, 4, 2, 64, torch.float32, max_tokens=8, device=DEV, y_perm_f32=True, act_split=True)
+    assert e.value.status == 3
+    ctx = gpu_lib.Context(128, 4, 2, 64, torch.bfloat16, max_tokens=8, device=DEV)
+    with pytest.raises(gpu_lib.MoeError) as e:
+        ctx.moe_set_ffn_variant(9)
+    assert e.value.status == 2
+
+
+# ------------------------------------------------------------ fp32 layer group
+GROUP_F32 = inputs.Workload("g_f32", H=256, E=8, K=2, I=512, n_layers=3, D=5, P=59, dtype="f32", chunk=16, seed=42)
+
+
+def test_fp32_group_teacher_forced_and_free_running(gpu_lib):
+    """The fp32 path between layers: per layer against the oracle fed the GPU's own fp32 input, the group call
+    against the chain of single-layer calls (bit for bit, both schedules), and the whole group against the
+    oracle's own free-running pass, which rounds to fp32 between layers."""
+    w = GROUP_F32
+    layers = [inputs.make_layer(w, l) for l in range(w.n_layers)]
+    dl = [dev_layer(L) for L in layers]
+    nl = [inputs.layer_to_numpy(L) for L in layers]
+    xd, xp = inputs.make_hidden(w)
+    ctx = make_ctx(gpu_lib, w, w.D + w.P)
+    x = torch.cat([xd, xp]).to(DEV)
+    for l in range(w.n_layers):
+        yd, yp = ctx.moe_group_forward([dl[l]], x[:w.D], x[w.D:], "layered")
+        y = torch.cat([yd, yp])
+        o_y, o_idx, _ = oracle.moe_layer(inputs.to_numpy(x), nl[l]["w_router"], None, nl[l]["w_gate_up"],
+                                         nl[l]["w_down"], w.K, residual=True)
+        idx, _ = ctx.moe_router_topk(x, dl[l]["w_router"])
+        assert (idx.cpu().numpy() == o_idx).all()
+        assert_close(y, o_y, "f32", f"fp32 layer {l}")
+        x = y
+    yd_l, yp_l = ctx.moe_group_forward(dl, xd.to(DEV), xp.to(DEV), "layered")
+    assert torch.equal(torch.cat([yd_l, yp_l]), x)
+    yd_c, yp_c = ctx.moe_group_forward(dl, xd.to(DEV), xp.to(DEV), "chunked", w.chunk)
+    assert torch.equal(yd_c, yd_l) and torch.equal(yp_c, yp_l)
+    o_d, o_p, _ = oracle.group_forward(nl, inputs.to_numpy(xd), inputs.to_numpy(xp), w.K, "layered")
+    assert_close(torch.cat([yd_l, yp_l]), np.concatenate([o_d, o_p]), "f32", "fp32 group, free-running")

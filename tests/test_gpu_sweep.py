@@ -45,12 +45,12 @@ def test_layer_against_oracle_and_schedules(gpu_lib, w):
     xdd, xpd = (xd.to(DEV) if w.D else None), (xp.to(DEV) if w.P else None)
     yd, yp = ctx.moe_group_forward([Ld], xdd, xpd, "layered")
     y = torch.cat([t for t in (yd, yp) if t.shape[0]])
-    o_y, o_idx, _, mag = oracle.moe_layer(inputs.to_numpy(x), Ln["w_router"], Ln["router_bias"], Ln["w_gate_up"],
-                                          Ln["w_down"], w.K, residual=w.residual, want_mag=True,
-                                          s_gate_up=Ln.get("s_gate_up"), s_down=Ln.get("s_down"))
+    o_y, o_idx, _ = oracle.moe_layer(inputs.to_numpy(x), Ln["w_router"], Ln["router_bias"], Ln["w_gate_up"],
+                                     Ln["w_down"], w.K, residual=w.residual,
+                                     s_gate_up=Ln.get("s_gate_up"), s_down=Ln.get("s_down"))
     idx, _ = ctx.moe_router_topk(x.to(DEV), Ld["w_router"], Ld["router_bias"])
     assert (idx.cpu().numpy() == o_idx).all()
-    assert_close(y, o_y, "bf16", w.name, mag=np.abs(o_y) + mag)
+    assert_close(y, o_y, "bf16", w.name)
     if w.P:
         for chunk in (7, 64):
             yd2, yp2 = ctx.moe_group_forward([Ld], xdd, xpd, "chunked", chunk)

@@ -1,8 +1,12 @@
 """GPU parity at the benchmark's full sizes, in the launch configuration bench.py times (same context
-size, same schedule, same kernel variants).  Routing, counts and permutation are checked bit for bit for
-EVERY token; floating-point outputs on sampled rows the oracle can compute one by one (tokens are
-independent in an MoE layer, so a row's value does not depend on the rest of the batch).  Layer groups
-are checked teacher-forced: for each layer the oracle is fed the GPU's own bf16 input to that layer.
+size, same schedule, same kernel variants, same y_perm format).  Routing, counts and permutation are
+checked bit for bit for EVERY token.  Floating-point outputs are checked on all rows where the oracle
+can afford it (`qwen3_layer`: 2112 rows; `decode_large`: all 256 rows of every layer) and otherwise on a
+stratified sample picked by permuted position (tests/sampling.py): the first and last row of every
+(expert, m-tile) of the launch plus random rows, at least 256 rows per layer.  Tokens are independent in
+an MoE layer, so a row's value does not depend on the rest of the batch.  Layer groups are checked
+teacher-forced: for each layer the oracle is fed the GPU's own bf16 input to that layer.  Every test
+prints how many compared elements needed the large-magnitude exception of tests/parity.py.
 """
 import numpy as np
 import pytest
@@ -11,15 +15,23 @@ import torch
 import oracle
 from paper_2510_08055_amd import inputs
 from parity import assert_close
+from sampling import stratified_tokens
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-def check_layer(ctx, w, L, x, y, rows, what):
-    """Layer output y = layer(x) on the GPU: routing of all rows bit-exact, sampled rows within tolerance."""
+def make_ctx(lib, w, max_tokens):
+    return lib.Context(w.H, w.E, w.K, w.I, inputs.torch_dtype(w.dtype), max_tokens=max_tokens, residual=w.residual,
+                       device=DEV, weight_format=w.weight_format, y_perm_f32=w.y_perm_f32, act_split=w.act_split)
+
+
+def check_layer(ctx, w, L, x, y, what, n_rows=256, tile_rows=256, all_rows=False):
+    """Layer output y = layer(x) on the GPU: routing of all rows bit-exact, compared rows within tolerance.
+    tile_rows: m-tile height of the grouped-GEMM variant this launch uses (for the stratified sample)."""
     Ln = inputs.layer_to_numpy(L)
     xn = inputs.to_numpy(x)
+    T = x.shape[0]
     idx, wt = ctx.moe_router_topk(x, L["w_router"], L["router_bias"])
     counts, offsets, perm, inv, _ = ctx.moe_permute(x, idx, want_x_perm=False)
     o_idx, o_w, gap = oracle.router_topk(xn, Ln["w_router"], Ln["router_bias"], w.K, want_gap=True)
@@ -29,30 +41,45 @@ def check_layer(ctx, w, L, x, y, rows, what):
     oc, oo, op, oi = oracle.permute(o_idx, w.E)
     assert (counts.cpu().numpy() == oc).all() and (offsets.cpu().numpy() == oo).all(), what
     assert (perm.cpu().numpy() == op).all() and (inv.cpu().numpy() == oi).all(), what
-    o_y, _, _, mag = oracle.moe_layer(xn[rows], Ln["w_router"], Ln["router_bias"], Ln["w_gate_up"], Ln["w_down"],
-                                      w.K, residual=w.residual, want_mag=True)
-    assert_close(y[torch.from_numpy(rows).to(DEV)], o_y, w.dtype, what, mag=np.abs(o_y) + mag)
-    return oc
+    rows = np.arange(T) if all_rows else stratified_tokens(oo, op, w.K, T, tile_rows, n_rows, seed=w.seed)
+    o_y, _, _ = oracle.moe_layer(xn[rows], Ln["w_router"], Ln["router_bias"], Ln["w_gate_up"], Ln["w_down"], w.K,
+                                 residual=w.residual, s_gate_up=Ln.get("s_gate_up"), s_down=Ln.get("s_down"))
+    st = assert_close(y[torch.from_numpy(rows).to(DEV)], o_y, w.dtype, what)
+    print(f"\n  {what}: {len(rows)} rows compared, {st['over_plain']} of {st['compared']} elements over 2e-2 "
+          f"(all at |ref| >= 8), max err below 8: {st['max_err_below_big']:.2e}, rel-L2 {st['rel_l2']:.2e}", end="")
+    return oc, st
 
 
-def sample_rows(T, n, seed):
-    rng = np.random.default_rng(seed)
-    return np.unique(np.concatenate([[0, T - 1], rng.choice(T, size=min(n, T), replace=False)]))
+def test_qwen3_layer_all_2112_rows(gpu_lib):
+    w = inputs.WORKLOADS["qwen3_layer"]
+    L = inputs.make_layer(w, 0, device=DEV)
+    xd, xp = inputs.make_hidden(w, device=DEV)
+    T = w.D + w.P
+    ctx = make_ctx(gpu_lib, w, T)
+    yd, yp = ctx.moe_group_forward([L], xd, xp, "layered")
+    oc, st = check_layer(ctx, w, L, torch.cat([xd, xp]), torch.cat([yd, yp]), "qwen3_layer", all_rows=True)
+    assert oc.sum() == T * w.K and abs(oc.mean() - T * w.K / w.E) < 1e-9      # Sec. 2.5: ~128 tokens per expert
+    assert st["over_plain"] == 0
+    # schedule equivalence at full size: chunked(512) routes and computes the same rows
+    yd_c, yp_c = ctx.moe_group_forward([L], xd, xp, "chunked", w.chunk)
+    assert torch.equal(yd_c, yd) and torch.equal(yp_c, yp)
 
 
-def test_qwen3_group8_layered_and_chunked(gpu_lib):
+def test_qwen3_group8_layered_and_chunked_768_rows_per_layer(gpu_lib):
     w = inputs.WORKLOADS["qwen3_group8"]
     layers = [inputs.make_layer(w, l, device=DEV) for l in range(w.n_layers)]
     xd, xp = inputs.make_hidden(w, device=DEV)
     T = w.D + w.P
-    ctx = gpu_lib.Context(w.H, w.E, w.K, w.I, torch.bfloat16, max_tokens=T, residual=w.residual, device=DEV)
-    # layer by layer (teacher-forced check of every layer at T = 8320 rows, ~520 rows per expert)
+    ctx = make_ctx(gpu_lib, w, T)
+    # layer by layer (teacher-forced check of every layer at T = 8320 rows, ~520 rows per expert: three
+    # m-tiles per expert, six tile-edge rows each)
     x = torch.cat([xd, xp])
     for l, L in enumerate(layers):
         yd, yp = ctx.moe_group_forward([L], x[:w.D], x[w.D:], "layered")
         y = torch.cat([yd, yp])
-        oc = check_layer(ctx, w, L, x, y, sample_rows(T, 10, l), f"qwen3_group8 layer {l}")
+        oc, st = check_layer(ctx, w, L, x, y, f"qwen3_group8 layer {l}", n_rows=256, tile_rows=256)
         assert oc.sum() == T * w.K and oc.mean() == 520        # Sec. 4.3: ~512 tokens per expert: compute-bound
+        assert st["over_plain"] == 0
         x = y
     # the group in one call, layered: one pass over every expert's weights per layer
     ctx.moe_reset_counters()
@@ -62,8 +89,7 @@ def test_qwen3_group8_layered_and_chunked(gpu_lib):
     per_pass = w.E * 3 * w.H * w.I * 2
     assert c_l.expert_bytes == w.n_layers * per_pass and c_l.iterations == 1
     # chunked(512): 16 iterations, every chunk re-streams every expert (Fig. 2: load = per-chunk load x chunks)
-    cc = gpu_lib.Context(w.H, w.E, w.K, w.I, torch.bfloat16, max_tokens=w.D + w.chunk, residual=w.residual,
-                         device=DEV)
+    cc = make_ctx(gpu_lib, w, w.D + w.chunk)
     yd_c, yp_c = cc.moe_group_forward(layers, xd, xp, "chunked", w.chunk)
     c_c = cc.moe_read_counters()
     assert c_c.iterations == 16 and c_c.expert_bytes == 16 * c_l.expert_bytes
@@ -73,14 +99,67 @@ def test_qwen3_group8_layered_and_chunked(gpu_lib):
     assert torch.equal(yd_2, yd_l) and torch.equal(yp_2, yp_l)
 
 
-def test_mixtral_zipf_layer(gpu_lib):
+def test_qwen3_group8_free_running_report(gpu_lib):
+    """Oracle and GPU each run the 8 layers on their own (no teacher forcing) over the decode rows and the
+    first 896 prompt rows.  The two states differ by a bf16 ulp in a fifth of the elements after a layer
+    (both round a result that differs by ~1.5e-3), which moves every logit of the next layer by a few 1e-3,
+    so a token's ordered routing row parts ways wherever two of its neighbouring logits are that close:
+    mostly two selected experts swapping places, sometimes another expert selected.  Reported: how many tokens
+    diverged (in order / in the selected set), at which layer first, and the oracle's margin there (smallest
+    gap between neighbouring logits around the decision).  Asserted: the first layer, which sees identical
+    inputs, routes identically; every divergence happens at an oracle margin below 2e-2 (logit spread 0.9);
+    tokens whose routing never diverged agree within the relative-L2 bar after 8 layers (element by element
+    they may be a few bf16 ulps of the residual stream apart, 0.016-0.03 each at magnitudes 2-8: the two
+    chains round a slightly different value at every layer; the count of such elements is reported)."""
+    w = inputs.WORKLOADS["qwen3_group8"]
+    n_tok = 1024
+    layers = [inputs.make_layer(w, l, device=DEV) for l in range(w.n_layers)]
+    xd, xp = inputs.make_hidden(w, device=DEV)
+    x_g = torch.cat([xd, xp[:n_tok - w.D]])
+    ctx = make_ctx(gpu_lib, w, n_tok)
+    x_o = inputs.to_numpy(x_g)                  # the oracle's own state: bf16 bit patterns between layers
+    diverged_at = np.full(n_tok, -1)
+    set_diverged = np.zeros(n_tok, dtype=bool)
+    margin = np.zeros(n_tok)
+    o_last = None
+    for l, L in enumerate(layers):
+        Ln = inputs.layer_to_numpy(L)
+        g_idx = ctx.moe_router_topk(x_g, L["w_router"])[0].cpu().numpy()
+        o_y, o_idx, _ = oracle.moe_layer(x_o, Ln["w_router"], None, Ln["w_gate_up"], Ln["w_down"], w.K, residual=True)
+        _, _, gap = oracle.router_topk(x_o, Ln["w_router"], None, w.K, want_gap=True)
+        differs = (g_idx != o_idx).any(axis=1)
+        set_diverged |= (np.sort(g_idx, axis=1) != np.sort(o_idx, axis=1)).any(axis=1)
+        new = differs & (diverged_at < 0)
+        diverged_at[new] = l
+        margin[new] = gap[new]
+        yd, yp = ctx.moe_group_forward([L], x_g[:w.D], x_g[w.D:], "layered")
+        x_g = torch.cat([yd, yp])
+        o_last = o_y
+        x_o = oracle.bf16_bits(oracle.round_bf16(o_y))
+    hit = diverged_at >= 0
+    print(f"\n  free-running, {n_tok} tokens x {w.n_layers} layers: {int(hit.sum())} tokens diverged in their ordered "
+          f"routing row ({int(set_diverged.sum())} of them in the selected set); first divergence per layer "
+          f"{np.bincount(diverged_at[hit], minlength=w.n_layers).tolist()}; oracle margins there: "
+          f"max {margin[hit].max():.2e}, median {np.median(margin[hit]):.2e}", end="")
+    assert diverged_at[hit].min() >= 1          # layer 0 sees identical inputs: no divergence there
+    assert (margin[hit] < 2e-2).all()
+    assert (~hit).sum() >= 100
+    g = x_g[torch.from_numpy(np.flatnonzero(~hit)).to(DEV)].double().cpu().numpy()
+    err = np.abs(g - o_last[~hit])
+    rel = np.linalg.norm(g - o_last[~hit]) / np.linalg.norm(o_last[~hit])
+    print(f"; the {int((~hit).sum())} same-route tokens after 8 layers: rel-L2 {rel:.2e}, max err {err.max():.2e}, "
+          f"{int((err > 2e-2).sum())} of {err.size} elements more than 2e-2 apart", end="")
+    assert rel <= 5e-3
+
+
+def test_mixtral_zipf_layer_256_rows(gpu_lib):
     w = inputs.WORKLOADS["mixtral_zipf"]
     L = inputs.make_layer(w, 0, device=DEV)
     xd, xp = inputs.make_hidden(w, device=DEV)
     T = w.D + w.P
-    ctx = gpu_lib.Context(w.H, w.E, w.K, w.I, torch.bfloat16, max_tokens=T, residual=w.residual, device=DEV)
+    ctx = make_ctx(gpu_lib, w, T)
     yd, yp = ctx.moe_group_forward([L], xd, xp, "layered")
-    oc = check_layer(ctx, w, L, torch.cat([xd, xp]), torch.cat([yd, yp]), sample_rows(T, 14, 3), "mixtral_zipf")
+    oc, _ = check_layer(ctx, w, L, torch.cat([xd, xp]), torch.cat([yd, yp]), "mixtral_zipf", n_rows=256, tile_rows=256)
     share = oc / oc.sum()
     assert np.abs(share - inputs.zipf_shares(w.E, w.zipf_s)).max() < 2e-3       # load-imbalanced on purpose
     assert oc.max() > 10 * oc.min()
@@ -88,10 +167,40 @@ def test_mixtral_zipf_layer(gpu_lib):
     assert torch.equal(yd_c, yd) and torch.equal(yp_c, yp)
 
 
-def test_decode_large_group(gpu_lib):
+def test_mixtral_zipf_with_a_plain_bf16_intermediate_reported(gpu_lib):
+    """The same layer with the intermediate in plain bf16 (the faster configuration, NOT the one whose parity is
+    claimed): routing and permutation exact, relative L2 within the bar, and a reported handful of elements
+    per ten thousand beyond the absolute bound, which is what the bf16 rounding of a 14336-wide intermediate
+    costs (~3e-3 rms per output on top of the output's own rounding)."""
+    import parity
+    w = inputs.WORKLOADS["mixtral_zipf_bf16act"]
+    L = inputs.make_layer(w, 0, device=DEV)
+    xd, xp = inputs.make_hidden(w, device=DEV)
+    T = w.D + w.P
+    ctx = make_ctx(gpu_lib, w, T)
+    yd, yp = ctx.moe_group_forward([L], xd, xp, "layered")
+    x, y = torch.cat([xd, xp]), torch.cat([yd, yp])
+    Ln, xn = inputs.layer_to_numpy(L), inputs.to_numpy(x)
+    idx, _ = ctx.moe_router_topk(x, L["w_router"], L["router_bias"])
+    o_idx, _ = oracle.router_topk(xn, Ln["w_router"], Ln["router_bias"], w.K)
+    assert (idx.cpu().numpy() == o_idx).all()
+    _, oo, op, _ = oracle.permute(o_idx, w.E)
+    rows = stratified_tokens(oo, op, w.K, T, 256, 256, seed=w.seed)
+    o_y, _, _ = oracle.moe_layer(xn[rows], Ln["w_router"], Ln["router_bias"], Ln["w_gate_up"], Ln["w_down"], w.K)
+    g = y[torch.from_numpy(rows).to(DEV)].double().cpu().numpy()
+    err = np.abs(g - o_y)
+    over = err > parity.bound_for(o_y, "bf16")
+    rel = np.linalg.norm(g - o_y) / np.linalg.norm(o_y)
+    print(f"\n  mixtral_zipf_bf16act: {int(over.sum())} of {o_y.size} elements over their bound "
+          f"(max err {err.max():.3e}, largest excess {float((err - parity.bound_for(o_y, 'bf16')).max()):.3e}), "
+          f"rel-L2 {rel:.2e}", end="")
+    assert rel <= 5e-3 and over.mean() < 2e-3 and err.max() < 5e-2
+
+
+def test_decode_large_group_all_rows(gpu_lib):
     w = inputs.WORKLOADS["decode_large"]
     xd, _ = inputs.make_hidden(w, device=DEV)
-    ctx = gpu_lib.Context(w.H, w.E, w.K, w.I, torch.bfloat16, max_tokens=w.D, residual=w.residual, device=DEV)
+    ctx = make_ctx(gpu_lib, w, w.D)
     x = xd
     layers = []
     active = 0
@@ -99,7 +208,7 @@ def test_decode_large_group(gpu_lib):
         L = inputs.make_layer(w, l, device=DEV)
         layers.append(L)
         y, _ = ctx.moe_group_forward([L], x, None, "layered")
-        oc = check_layer(ctx, w, L, x, y, sample_rows(w.D, 6, l), f"decode_large layer {l}")
+        oc, _ = check_layer(ctx, w, L, x, y, f"decode_large layer {l}", all_rows=True)
         active += int((oc > 0).sum())
         x = y
     ctx.moe_reset_counters()
@@ -110,15 +219,47 @@ def test_decode_large_group(gpu_lib):
     assert active >= 0.99 * w.n_layers * w.E        # 256 tokens x top-4 over 128 experts touch (nearly) all of them
 
 
-def test_gptoss_layer(gpu_lib):
+def test_gptoss_layer_256_rows(gpu_lib):
     # the second model family of Table 3: 32 experts, top-4, hidden size 2880 (264 rows per expert here)
     w = inputs.WORKLOADS["gptoss_layer"]
     L = inputs.make_layer(w, 0, device=DEV)
     xd, xp = inputs.make_hidden(w, device=DEV)
     T = w.D + w.P
-    ctx = gpu_lib.Context(w.H, w.E, w.K, w.I, torch.bfloat16, max_tokens=T, residual=w.residual, device=DEV)
+    ctx = make_ctx(gpu_lib, w, T)
     yd, yp = ctx.moe_group_forward([L], xd, xp, "layered")
-    oc = check_layer(ctx, w, L, torch.cat([xd, xp]), torch.cat([yd, yp]), sample_rows(T, 12, 5), "gptoss_layer")
+    oc, _ = check_layer(ctx, w, L, torch.cat([xd, xp]), torch.cat([yd, yp]), "gptoss_layer", n_rows=256, tile_rows=256)
     assert oc.sum() == T * w.K and oc.min() > 0
     yd_c, yp_c = ctx.moe_group_forward([L], xd, xp, "chunked", w.chunk)
     assert torch.equal(yd_c, yd) and torch.equal(yp_c, yp)
+
+
+def test_decode_large_w4_layer0_all_rows(gpu_lib):
+    """The decode-heavy shape with MXFP4 expert weights (streaming kernel shape): every row of layer 0."""
+    w = inputs.WORKLOADS["decode_large_w4"]
+    xd, _ = inputs.make_hidden(w, device=DEV)
+    ctx = make_ctx(gpu_lib, w, w.D)
+    L = inputs.make_layer(w, 0, device=DEV)
+    ctx.moe_reset_counters()
+    y, _ = ctx.moe_group_forward([L], xd, None, "layered")
+    c = ctx.moe_read_counters()
+    oc, _ = check_layer(ctx, w, L, xd, y, "decode_large_w4 layer 0", all_rows=True)
+    active = int((oc > 0).sum())
+    assert c.active_experts_total == active and c.expert_bytes == active * 3 * w.H * w.I * 17 // 32
+
+
+def test_gptoss_layer_w4_256_rows(gpu_lib):
+    """The hybrid batch of the second model family with its 4-bit expert weights (64-row tile shape)."""
+    w = inputs.WORKLOADS["gptoss_layer_w4"]
+    xd, xp = inputs.make_hidden(w, device=DEV)
+    ctx = make_ctx(gpu_lib, w, w.D + w.P)
+    L = inputs.make_layer(w, 0, device=DEV)
+    ctx.moe_reset_counters()
+    yd, yp = ctx.moe_group_forward([L], xd, xp, "layered")
+    c = ctx.moe_read_counters()
+    y = torch.cat([yd, yp])
+    oc, _ = check_layer(ctx, w, L, torch.cat([xd, xp]), y, "gptoss_layer_w4", n_rows=256, tile_rows=64)
+    active = int((oc > 0).sum())
+    assert c.active_experts_total == active and c.expert_bytes == active * 3 * w.H * w.I * 17 // 32
+    # the chunked schedule (streaming shape on the small chunks) gives the same bits
+    yd2, yp2 = ctx.moe_group_forward([L], xd, xp, "chunked", 128)
+    assert torch.equal(torch.cat([yd2, yp2]), y)

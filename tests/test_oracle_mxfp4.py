@@ -57,9 +57,9 @@ def test_generated_mxfp4_weights_have_the_stated_shape_and_scale():
     L = inputs.layer_to_numpy(inputs.make_layer(W4, 0))
     assert L["w_gate_up"].shape == (W4.E, 2 * W4.I, W4.H // 2) and L["s_gate_up"].shape == (W4.E, 2 * W4.I, W4.H // 32)
     assert L["w_down"].shape == (W4.E, W4.H, W4.I // 2) and L["s_down"].shape == (W4.E, W4.H, W4.I // 32)
-    assert L["s_gate_up"].min() >= 119 and L["s_gate_up"].max() <= 121
+    assert L["s_gate_up"].min() >= 118 and L["s_gate_up"].max() <= 120
     w = oracle.mxfp4_dequant(L["w_gate_up"], L["s_gate_up"])
-    assert 0.015 < w.std() < 0.035                 # the scale of the N(0, 0.02) weights of the other workloads
+    assert 0.012 < w.std() < 0.02                  # just under the N(0, 0.02) weights of the other workloads
 
 
 @pytest.mark.parametrize("residual", [False, True])
