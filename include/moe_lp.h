@@ -135,6 +135,19 @@ moe_status moe_router_topk(moe_ctx *ctx, const void *x, int64_t T, const void *w
                            int32_t *topk_idx, float *topk_w, void *stream);
 
 /*
+ * moe_router_topk for callers that cannot allocate device memory and have no workspace to hand over (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): no context; the logits
+ * live in a static device array of the library (4 MiB per GPU, held until the process ends), so
+ * T * cfg->E must not exceed 524288 (MOE_ERR_WORKSPACE otherwise, before anything is launched).  Same
+ * arithmetic, same kernels and same results as moe_router_topk with a context of this cfg; H, E, K,
+ * dtype and renormalize of cfg are read.  The call allocates nothing, on the host or the device.  All
+ * calls on one GPU share the array: calls that overlap in time on one GPU (different streams, or
+ * different threads) race; serialise them.
+ */
+moe_status moe_router_topk_noalloc(const moe_config *cfg, const void *x, int64_t T, const void *w_router,
+                                   const float *bias, int32_t *topk_idx, float *topk_w, void *stream);
+
+/*
  * Token permutation (Sec. 3.1: the tokens routed to each expert form that expert's batch).
  * The T*K assignments (t, j) are listed by expert, then token, then slot:
  *   counts [E], offsets [E+1] (exclusive running sum, offsets[E] = T*K),

@@ -20,7 +20,7 @@ MOE_SCHED_CHUNKED, MOE_SCHED_LAYERED = 0, 1
 MOE_W_DTYPE, MOE_W_MXFP4 = 0, 1
 WEIGHT_FORMATS = {"": MOE_W_DTYPE, "dtype": MOE_W_DTYPE, "mxfp4": MOE_W_MXFP4}
 
-EXPORTS = ["moe_workspace_bytes", "moe_create", "moe_destroy", "moe_router_topk", "moe_permute",
+EXPORTS = ["moe_workspace_bytes", "moe_create", "moe_destroy", "moe_router_topk", "moe_router_topk_noalloc", "moe_permute",
            "moe_grouped_ffn", "moe_grouped_ffn_mxfp4", "moe_combine", "moe_group_forward", "moe_num_layer_groups", "moe_layer_groups",
            "moe_stack_forward", "moe_read_counters", "moe_reset_counters",
            "moe_kernel_timing", "moe_read_kernel_timing", "moe_ffn_variant", "moe_set_ffn_variant",
@@ -88,6 +88,7 @@ def load():
     L.moe_create.argtypes = [ctypes.POINTER(CConfig), i64, vp, ctypes.c_size_t, vp, ctypes.POINTER(vp)]
     L.moe_destroy.argtypes = [vp]
     L.moe_router_topk.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp]
+    L.moe_router_topk_noalloc.argtypes = [ctypes.POINTER(CConfig), vp, i64, vp, vp, vp, vp, vp]
     L.moe_permute.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp, vp, vp]
     L.moe_grouped_ffn.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp]
     L.moe_grouped_ffn_mxfp4.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp, vp, vp]
@@ -159,6 +160,22 @@ def workspace_bytes(H, E, K, I, dtype, max_tokens, renormalize=True, residual=Tr
     out = ctypes.c_size_t(0)
     _check(load().moe_workspace_bytes(ctypes.byref(cfg), max_tokens, ctypes.byref(out)), "moe_workspace_bytes")
     return out.value
+
+
+def moe_router_topk_noalloc(x, w_router, bias, K, renormalize=True, topk_idx=None, topk_w=None):
+    """The router without a context or workspace (the library's static scratch holds the logits).  The outputs
+    may be passed in, so that the call itself allocates nothing."""
+    T, H = x.shape
+    E = w_router.shape[0]
+    cfg = CConfig(H, E, K, 8, _dtype_code(x.dtype), int(renormalize), 0, MOE_W_DTYPE, 0, 0)
+    if topk_idx is None:
+        topk_idx = torch.empty((T, K), dtype=torch.int32, device=x.device)
+    if topk_w is None:
+        topk_w = torch.empty((T, K), dtype=torch.float32, device=x.device)
+    with torch.cuda.device(x.device):
+        _check(load().moe_router_topk_noalloc(ctypes.byref(cfg), _ptr(x), T, _ptr(w_router), _ptr(bias), _ptr(topk_idx),
+                                              _ptr(topk_w), _stream()), "moe_router_topk_noalloc")
+    return topk_idx, topk_w
 
 
 class Context:

@@ -1,6 +1,7 @@
 // C ABI of the MoE hot path: argument checks, workspace carving and the layer-group driver
 // for the chunked (Sec. 2.3) and layered (Sec. 4.1-4.2) prefill schedules.  All arithmetic
 // happens in the kernels of router.hip / permute.hip / ffn.hip / combine.hip.
+#include <mutex>
 #include <new>
 #include <utility>
 #include <vector>
@@ -30,6 +31,13 @@ struct moe_ctx {
     std::vector<std::pair<hipEvent_t, hipEvent_t>> timing[MOE_KERNEL_COUNT];
     std::vector<std::pair<hipEvent_t, hipEvent_t>> event_pool;
 };
+
+// Scratch of moe_router_topk_noalloc: the router's scratch of one call, i.e. the fp64 logits [T, E], or the
+// candidate lists (counts [T] int32, then lists [T, E] uint16) of the two-pass form.  One copy per GPU, held
+// until the process ends; in host code the name below is only a handle for hipGetSymbolAddress, never an
+// address.
+constexpr int64_t kNoallocMaxLogits = (int64_t)1 << 19;      // T * E <= 524288: 4 MiB of logits
+static __device__ __align__(256) double scratch[kNoallocMaxLogits];
 
 namespace {
 
@@ -321,6 +329,49 @@ moe_status moe_router_topk(moe_ctx* ctx, const void* x, int64_t T, const void* w
     hipError_t e = launch_router_logits(g.dtype, single_src(x), T, g.H, w_router, bias, g.E, ctx->logits, nullptr, 0, s);
     if (e != hipSuccess) return MOE_ERR_DEVICE;
     return dev(launch_topk(ctx->logits, T, g.E, g.K, g.renormalize, topk_idx, topk_w, nullptr, s));
+}
+
+moe_status moe_router_topk_noalloc(const moe_config* cfg, const void* x, int64_t T, const void* w_router,
+                                   const float* bias, int32_t* topk_idx, float* topk_w, void* stream)
+{
+    moe_status st = check_cfg(cfg);
+    if (st != MOE_OK) return st;
+    if (T < 0) return MOE_ERR_SHAPE;
+    if (T * (int64_t)cfg->E > kNoallocMaxLogits) return MOE_ERR_WORKSPACE;      // the static scratch holds T * E logits
+    if (T == 0) return MOE_OK;
+    if (!x || !w_router || !topk_idx || !topk_w) return MOE_ERR_NULL;
+    if (misaligned(x) || misaligned(w_router)) return MOE_ERR_ALIGN;
+    // device address of this GPU's copy of the scratch array, looked up once per device
+    static std::mutex mu;
+    static double* dev_scratch[kMaxDevices] = {};
+    int d = 0;
+    if (hipGetDevice(&d) != hipSuccess || d < 0 || d >= kMaxDevices) return MOE_ERR_DEVICE;
+    double* logits = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(mu);
+        if (!dev_scratch[d]) {
+            void* p = nullptr;
+            if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return MOE_ERR_DEVICE;
+            dev_scratch[d] = static_cast<double*>(p);
+        }
+        logits = dev_scratch[d];
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (router_two_pass_ok(cfg->dtype, cfg->renormalize)) {
+        // counts in the first T * 4 bytes (T <= T * E), the lists behind them from the next 256-byte boundary:
+        // T * 4 + 256 + T * E * 2 <= 8 * T * E whenever E >= 2; a single expert takes the full pass below
+        if (cfg->E >= 2) {
+            char* base = reinterpret_cast<char*>(logits);
+            int32_t* cnt = reinterpret_cast<int32_t*>(base);
+            uint16_t* lists = reinterpret_cast<uint16_t*>(base + up((size_t)T * 4));
+            if (up((size_t)T * 4) + (size_t)T * cfg->E * 2 <= (size_t)kNoallocMaxLogits * sizeof(double))
+                return dev(launch_router_two_pass(single_src(x), T, cfg->H, w_router, bias, cfg->E, cfg->K, cnt, lists,
+                                                  topk_idx, topk_w, nullptr, nullptr, 0, s));
+        }
+    }
+    hipError_t e = launch_router_logits(cfg->dtype, single_src(x), T, cfg->H, w_router, bias, cfg->E, logits, nullptr, 0, s);
+    if (e != hipSuccess) return MOE_ERR_DEVICE;
+    return dev(launch_topk(logits, T, cfg->E, cfg->K, cfg->renormalize, topk_idx, topk_w, nullptr, s));
 }
 
 moe_status moe_permute(moe_ctx* ctx, const void* x, const int32_t* topk_idx, int64_t T, int32_t* counts,

@@ -84,6 +84,20 @@ def test_create_rejects_bad_arguments_before_touching_the_gpu():
     assert lib.moe_set_ffn_variant(None, 0) == 1
 
 
+def test_router_topk_noalloc_rejects_bad_arguments_before_touching_the_gpu():
+    lib = binding.load()
+    cfg = binding.CConfig(256, 128, 8, 512, 1, 1, 1)
+    fake = ctypes.c_void_p(0x10000)      # never dereferenced: every call below fails its checks first
+    assert lib.moe_router_topk_noalloc(None, fake, 4, fake, None, fake, fake, None) == 1
+    assert lib.moe_router_topk_noalloc(ctypes.byref(cfg), fake, -1, fake, None, fake, fake, None) == 2
+    assert lib.moe_router_topk_noalloc(ctypes.byref(cfg), fake, 4097, fake, None, fake, fake, None) == 5   # 4097 * 128 logits
+    assert lib.moe_router_topk_noalloc(ctypes.byref(cfg), None, 4, fake, None, fake, fake, None) == 1
+    assert lib.moe_router_topk_noalloc(ctypes.byref(cfg), ctypes.c_void_p(0x10008), 4, fake, None, fake, fake, None) == 4
+    assert lib.moe_router_topk_noalloc(ctypes.byref(cfg), None, 0, None, None, None, None, None) == 0      # no rows: a no-op
+    bad = binding.CConfig(256, 8, 9, 512, 1, 1, 1)
+    assert lib.moe_router_topk_noalloc(ctypes.byref(bad), fake, 4, fake, None, fake, fake, None) == 2
+
+
 def test_group_count_rule_and_layer_groups_are_host_arithmetic():
     # Sec. 4.4: N_lg(L) = max(1, ceil(L / 512)): 8192 tokens -> 16 groups, 512 tokens -> 1 group
     assert binding.moe_num_layer_groups(8192, 48, 512) == 16
