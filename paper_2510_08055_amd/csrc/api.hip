@@ -17,8 +17,7 @@ struct moe_ctx {
     // workspace slices (device)
     unsigned long long* d_active_total;
     double* logits;
-    int32_t *idx, *counts, *offsets, *perm, *inv, *tile_hist, *cand_cnt;
-    uint16_t* cand;
+    int32_t *idx, *counts, *offsets, *perm, *inv, *tile_hist;
     float* w;
     void *xa, *xb, *act, *y_perm;
     // host-side counters (everything the host already knows)
@@ -32,10 +31,8 @@ struct moe_ctx {
     std::vector<std::pair<hipEvent_t, hipEvent_t>> event_pool;
 };
 
-// Scratch of moe_router_topk_noalloc: the router's scratch of one call, i.e. the fp64 logits [T, E], or the
-// candidate lists (counts [T] int32, then lists [T, E] uint16) of the two-pass form.  One copy per GPU, held
-// until the process ends; in host code the name below is only a handle for hipGetSymbolAddress, never an
-// address.
+// Scratch of moe_router_topk_noalloc: the fp64 logits [T, E] of one call.  One copy per GPU, held until the
+// process ends; in host code the name below is only a handle for hipGetSymbolAddress, never an address.
 constexpr int64_t kNoallocMaxLogits = (int64_t)1 << 19;      // T * E <= 524288: 4 MiB of logits
 static __device__ __align__(256) double scratch[kNoallocMaxLogits];
 
@@ -64,7 +61,7 @@ moe_status check_cfg(const moe_config* c)
 }
 
 struct Layout {
-    size_t counters, logits, cand_cnt, cand, idx, w, counts, offsets, perm, inv, tile_hist, xa, xb, act, y_perm, total;
+    size_t counters, logits, idx, w, counts, offsets, perm, inv, tile_hist, xa, xb, act, y_perm, total;
 };
 
 Layout carve(const moe_config& c, int64_t Tm)
@@ -76,11 +73,7 @@ Layout carve(const moe_config& c, int64_t Tm)
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o += up(bytes); return at; };
     L.counters = take(256);
-    // the router's scratch: fp64 logits [T, E] (full fp64 pass) or candidate lists (two-pass form)
-    const bool two_pass = router_two_pass_ok(c.dtype, c.renormalize);
-    L.logits = take(two_pass ? 0 : (size_t)Tm * c.E * sizeof(double));
-    L.cand_cnt = take(two_pass ? (size_t)Tm * 4 : 0);
-    L.cand = take(two_pass ? (size_t)Tm * c.E * 2 : 0);
+    L.logits = take((size_t)Tm * c.E * sizeof(double));
     L.idx = take(Am * 4);
     L.w = take(Am * 4);
     L.counts = take((size_t)c.E * 4);
@@ -150,27 +143,15 @@ moe_status run_layer(moe_ctx* c, const moe_layer& L, RowSrc x, int64_t T, void* 
     const int n_perm_tiles = (int)((A + kPermTile - 1) / kPermTile);
     const bool fused_hist = n_perm_tiles > 1;
     hipError_t e;
-    if (router_two_pass_ok(g.dtype, g.renormalize)) {
-        // (both passes are timed as the router-logits kernel; nothing is recorded for the top-k id)
+    {
         Timed t(c, MOE_KERNEL_ROUTER_LOGITS, s);
-        e = launch_router_two_pass(x, T, g.H, L.w_router, L.router_bias, g.E, g.K, c->cand_cnt, c->cand, c->idx, c->w,
-                                   fused_hist ? c->tile_hist : nullptr, c->tile_hist, fused_hist ? n_perm_tiles * g.E : 0,
-                                   s);
-    } else {
-        {
-            Timed t(c, MOE_KERNEL_ROUTER_LOGITS, s);
-            e = launch_router_logits(g.dtype, x, T, g.H, L.w_router, L.router_bias, g.E, c->logits, c->tile_hist,
-                                     fused_hist ? n_perm_tiles * g.E : 0, s);
-        }
-        if (e != hipSuccess) return MOE_ERR_DEVICE;
-        Timed t(c, MOE_KERNEL_TOPK, s);
-        e = launch_topk(c->logits, T, g.E, g.K, g.renormalize, c->idx, c->w, fused_hist ? c->tile_hist : nullptr, s);
+        e = launch_router_logits(g.dtype, x, T, g.H, L.w_router, L.router_bias, g.E, c->logits, c->tile_hist,
+                                 fused_hist ? n_perm_tiles * g.E : 0, s);
     }
     if (e != hipSuccess) return MOE_ERR_DEVICE;
     {
-        Timed t(c, MOE_KERNEL_PERMUTE, s);
-        e = launch_permute(c->idx, A, g.E, c->counts, c->offsets, c->perm, c->inv, c->tile_hist, fused_hist,
-                           c->d_active_total, s);
+        Timed t(c, MOE_KERNEL_TOPK, s);
+        e = launch_topk(c->logits, T, g.E, g.K, g.renormalize, c->idx, c->w, fused_hist ? c->tile_hist : nullptr, s);
     }
     if (e != hipSuccess) return MOE_ERR_DEVICE;
     // the activation rows are gathered inside the gate_up GEMM's tile loads: no x_perm round trip
@@ -280,8 +261,6 @@ moe_status moe_create(const moe_config* cfg, int64_t max_tokens, void* workspace
     c->esz = cfg->dtype == MOE_BF16 ? 2 : 4;
     c->d_active_total = reinterpret_cast<unsigned long long*>(b + L.counters);
     c->logits = reinterpret_cast<double*>(b + L.logits);
-    c->cand_cnt = reinterpret_cast<int32_t*>(b + L.cand_cnt);
-    c->cand = reinterpret_cast<uint16_t*>(b + L.cand);
     c->idx = reinterpret_cast<int32_t*>(b + L.idx);
     c->w = reinterpret_cast<float*>(b + L.w);
     c->counts = reinterpret_cast<int32_t*>(b + L.counts);
@@ -323,9 +302,6 @@ moe_status moe_router_topk(moe_ctx* ctx, const void* x, int64_t T, const void* w
     if (misaligned(x) || misaligned(w_router)) return MOE_ERR_ALIGN;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const moe_config& g = ctx->cfg;
-    if (router_two_pass_ok(g.dtype, g.renormalize))
-        return dev(launch_router_two_pass(single_src(x), T, g.H, w_router, bias, g.E, g.K, ctx->cand_cnt, ctx->cand,
-                                          topk_idx, topk_w, nullptr, nullptr, 0, s));
     hipError_t e = launch_router_logits(g.dtype, single_src(x), T, g.H, w_router, bias, g.E, ctx->logits, nullptr, 0, s);
     if (e != hipSuccess) return MOE_ERR_DEVICE;
     return dev(launch_topk(ctx->logits, T, g.E, g.K, g.renormalize, topk_idx, topk_w, nullptr, s));
@@ -357,18 +333,6 @@ moe_status moe_router_topk_noalloc(const moe_config* cfg, const void* x, int64_t
         logits = dev_scratch[d];
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (router_two_pass_ok(cfg->dtype, cfg->renormalize)) {
-        // counts in the first T * 4 bytes (T <= T * E), the lists behind them from the next 256-byte boundary:
-        // T * 4 + 256 + T * E * 2 <= 8 * T * E whenever E >= 2; a single expert takes the full pass below
-        if (cfg->E >= 2) {
-            char* base = reinterpret_cast<char*>(logits);
-            int32_t* cnt = reinterpret_cast<int32_t*>(base);
-            uint16_t* lists = reinterpret_cast<uint16_t*>(base + up((size_t)T * 4));
-            if (up((size_t)T * 4) + (size_t)T * cfg->E * 2 <= (size_t)kNoallocMaxLogits * sizeof(double))
-                return dev(launch_router_two_pass(single_src(x), T, cfg->H, w_router, bias, cfg->E, cfg->K, cnt, lists,
-                                                  topk_idx, topk_w, nullptr, nullptr, 0, s));
-        }
-    }
     hipError_t e = launch_router_logits(cfg->dtype, single_src(x), T, cfg->H, w_router, bias, cfg->E, logits, nullptr, 0, s);
     if (e != hipSuccess) return MOE_ERR_DEVICE;
     return dev(launch_topk(logits, T, cfg->E, cfg->K, cfg->renormalize, topk_idx, topk_w, nullptr, s));

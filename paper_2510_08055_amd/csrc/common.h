@@ -62,14 +62,6 @@ hipError_t launch_router_logits(int dtype, RowSrc x, int64_t T, int H, const voi
 hipError_t launch_topk(const double* logits, int64_t T, int E, int K, int renorm, int32_t* idx, float* w,
                        int32_t* tile_hist, hipStream_t s);
 
-// The two-pass form of the two calls above (bf16 inputs, renormalised weights): a screening pass on the bf16
-// matrix cores, then exact fp64 logits for the experts that can be selected, top-k and weights.
-// cand_cnt [T] and cand [T, E] are scratch; zero_buf / tile_hist as above.
-bool router_two_pass_ok(int dtype, int renorm);
-hipError_t launch_router_two_pass(RowSrc x, int64_t T, int H, const void* w_router, const float* bias, int E, int K,
-                                  int32_t* cand_cnt, uint16_t* cand, int32_t* idx, float* w, int32_t* tile_hist,
-                                  int32_t* zero_buf, int zero_n, hipStream_t s);
-
 // permute.hip
 constexpr int kPermTile = 8192;  // assignments per block of the permutation kernels
 // hist_ready: tile_hist already holds the per-tile histograms (the top-k kernel counted them)

@@ -381,295 +381,6 @@ __global__ __launch_bounds__(kTopkWaves * 64) void topk_rows_kernel(const double
 }
 
 
-// ----------------------------------------------------------------------------------------------
-// Two-pass router for bf16 inputs with renormalised weights: the same fp64 decisions for a fraction of
-// the fp64 work.  The K selected experts, their order and their weights only need EXACT logits of the
-// experts that can be among the K largest; which those are is settled with cheap approximate logits and
-// a rigorous error bound.
-//
-// Pass A (router_screen_kernel): approximate logits f[t,e] on the bf16 matrix cores (fp32 accumulate).
-// A product of two bf16 values is exact in fp32, so f differs from the exact logit z only by the
-// roundings of the additions: |f - z| <= H u sum_h |x_h w_h| <= H u |x_t| |w_e| =: d[t,e] (u = 2^-23, twice
-// the unit roundoff: holds for any order of the additions and for truncating adders; Cauchy-Schwarz for
-// the second step; the squared norms come out of the same MFMA stream as the diagonals of x x^T and
-// w w^T and are inflated for their own rounding; the bias adds its own term).  With L = the K-th
-// largest of f - d over a token's experts, at least K experts have z >= L, so an expert with
-// f + d < L is strictly below K others and cannot be selected: the rest, K plus a fraction of an
-// expert per token at these logit spreads, are the token's candidates.
-// Pass B (router_exact_topk_kernel): for the candidates only, the fp64 dot product with a summation
-// order fixed by H alone (batch-invariant, as before), then the K largest under (logit desc, index asc)
-// and their softmax weights, exactly as the full kernel computes them; per-tile expert histogram as
-// in the top-k kernels.  Whatever the screen does, the decisions are those of the exact logits.
-// ----------------------------------------------------------------------------------------------
-typedef __bf16 bf16x8_r __attribute__((ext_vector_type(8)));
-typedef float float4_r __attribute__((ext_vector_type(4)));
-
-constexpr int kScreenTokens = 16;      // tokens per block of pass A
-
-template <int CT>   // expert column tiles (of 16) per wave: wave w owns tiles w, w + 4, ...
-__global__ __launch_bounds__(256) void router_screen_kernel(RowSrc x, int64_t n_tok, int H,
-                                                            const bf16_t* __restrict__ wr,
-                                                            const float* __restrict__ bias, int E, int K,
-                                                            int32_t* __restrict__ cand_cnt,
-                                                            uint16_t* __restrict__ cand,
-                                                            int32_t* __restrict__ zero_buf, int zero_n)
-{
-    constexpr int EP = CT * 64;                 // experts covered (padded)
-    constexpr int NPL = EP / 16;                // values per lane in the selection phase
-    extern __shared__ float sm[];               // lo [16][EP], hi [16][EP], xn2 [16], wn2 [EP]
-    float* lo = sm;
-    float* hi = sm + kScreenTokens * EP;
-    float* xn2 = hi + kScreenTokens * EP;
-    float* wn2 = xn2 + kScreenTokens;
-    if (blockIdx.x == 0)
-        for (int i = threadIdx.x; i < zero_n; i += 256) zero_buf[i] = 0;
-    const int lane = lane_id();
-    const int wave = threadIdx.x >> 6;
-    const int r = lane & 15, q = lane >> 4;
-    const int64_t t0 = (int64_t)blockIdx.x * kScreenTokens;
-    const int64_t tr = (t0 + r < n_tok) ? (t0 + r) : (n_tok - 1);      // clamp: loads stay in bounds
-    const bf16_t* xp = row_ptr<bf16_t>(x, tr, H) + q * 8;
-    const bf16_t* wp[CT];
-#pragma unroll
-    for (int i = 0; i < CT; ++i) {
-        const int e = (wave + 4 * i) * 16 + r;
-        wp[i] = wr + (int64_t)(e < E ? e : E - 1) * H + q * 8;
-    }
-    float4_r acc[CT], gw[CT], gx = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int i = 0; i < CT; ++i) {
-        acc[i] = float4_r{0.f, 0.f, 0.f, 0.f};
-        gw[i] = float4_r{0.f, 0.f, 0.f, 0.f};
-    }
-    // lane (r, q) feeds k-values [k0 + 8 q, k0 + 8 q + 8) of row r to both operands of a 16 x 16 x 32 MFMA
-    const u32x4_t zero4 = {0, 0, 0, 0};
-    for (int k0 = 0; k0 < H; k0 += 32) {
-        const bool in = k0 + q * 8 < H;         // H is a multiple of 8: a lane's 8 values are in or out together
-        const u32x4_t xr = in ? *reinterpret_cast<const u32x4_t*>(xp + k0) : zero4;
-        u32x4_t wv[CT];
-#pragma unroll
-        for (int i = 0; i < CT; ++i) wv[i] = in ? *reinterpret_cast<const u32x4_t*>(wp[i] + k0) : zero4;
-        const bf16x8_r xa = __builtin_bit_cast(bf16x8_r, xr);
-        if (wave == 0) gx = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa, xa, gx, 0, 0, 0);
-#pragma unroll
-        for (int i = 0; i < CT; ++i) {
-            const bf16x8_r wb = __builtin_bit_cast(bf16x8_r, wv[i]);
-            acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa, wb, acc[i], 0, 0, 0);
-            gw[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wb, wb, gw[i], 0, 0, 0);
-        }
-    }
-    // result layout: lane l, element v holds row 4 (l / 16) + v (first operand's row), column l % 16
-    // squared norms: the diagonals of the two Gram tiles
-#pragma unroll
-    for (int v = 0; v < 4; ++v) {
-        if (4 * q + v == r) {
-            if (wave == 0) xn2[r] = gx[v];
-#pragma unroll
-            for (int i = 0; i < CT; ++i) wn2[(wave + 4 * i) * 16 + r] = gw[i][v];
-        }
-    }
-    __syncthreads();
-    {
-        const float NEGF = -__builtin_huge_valf();
-        const float gamma = (float)H * 1.1920929e-7f;      // H * 2^-23
-#pragma unroll
-        for (int i = 0; i < CT; ++i) {
-            const int e = (wave + 4 * i) * 16 + r;
-            const float b = (bias && e < E) ? bias[e] : 0.f;
-            const float nw = wn2[e];
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int row = 4 * q + v;
-                const float f = acc[i][v] + b;
-                // bound of |f - z|: the additions of the dot product (norms inflated by 2 % for their own
-                // rounding), the addition of the bias, the roundings of the next two lines, and a floor
-                const float d = 1.02f * gamma * __builtin_sqrtf(xn2[row] * nw) + 4.8e-7f * (fabsf(acc[i][v]) + fabsf(b)) + 1e-9f;
-                lo[row * EP + e] = (e < E) ? f - d : NEGF;
-                hi[row * EP + e] = (e < E) ? f + d : NEGF;
-            }
-        }
-    }
-    __syncthreads();
-    // selection: one token per 16-lane row, 4 tokens per wave; lane c holds experts c, c + 16, ...
-    const int c = r;
-    const int row = wave * 4 + q;
-    const int64_t t = t0 + row;
-    const float NEGF = -__builtin_huge_valf();
-    float v[NPL];
-#pragma unroll
-    for (int i = 0; i < NPL; ++i) v[i] = lo[row * EP + c + 16 * i];
-    float L = NEGF;
-    for (int j = 0; j < K; ++j) {
-        float bv = v[0];
-        int bi = 0;
-#pragma unroll
-        for (int i = 1; i < NPL; ++i)
-            if (v[i] > bv) { bv = v[i]; bi = i; }
-        int be = c + 16 * bi;
-        // row-wide maximum of (value, expert): any fixed total order will do here, the K-th largest VALUE is what counts
-        auto step = [&](float ov, int oe) {
-            if (ov > bv || (ov == bv && oe < be)) { bv = ov; be = oe; }
-        };
-        step(__builtin_bit_cast(float, dpp_mov<kDppXor1>(__builtin_bit_cast(int, bv))), dpp_mov<kDppXor1>(be));
-        step(__builtin_bit_cast(float, dpp_mov<kDppXor2>(__builtin_bit_cast(int, bv))), dpp_mov<kDppXor2>(be));
-        step(__builtin_bit_cast(float, dpp_mov<kDppHalfMirror>(__builtin_bit_cast(int, bv))), dpp_mov<kDppHalfMirror>(be));
-        step(__builtin_bit_cast(float, dpp_mov<kDppMirror>(__builtin_bit_cast(int, bv))), dpp_mov<kDppMirror>(be));
-        L = bv;
-        if ((be & 15) == c) {
-            const int slot = be >> 4;
-#pragma unroll
-            for (int i = 0; i < NPL; ++i)
-                if (i == slot) v[i] = NEGF;
-        }
-    }
-    // candidates: experts whose upper bound reaches L, listed by ascending expert index
-    int n = 0;
-    const int shift = q * 16;
-    const unsigned below = (1u << c) - 1u;
-#pragma unroll
-    for (int i = 0; i < NPL; ++i) {
-        const int e = c + 16 * i;
-        const bool is = e < E && hi[row * EP + e] >= L;
-        const unsigned m = (unsigned)((__ballot(is) >> shift) & 0xffffull);
-        if (is && t < n_tok) cand[t * E + n + __popc(m & below)] = (uint16_t)e;
-        n += __popc(m);
-    }
-    if (c == 0 && t < n_tok) cand_cnt[t] = n;
-}
-
-// Fixed-order sum over the 64 lanes of a wave (every lane ends with the same bits: a + b == b + a).
-__device__ __forceinline__ double wave_sum(double v)
-{
-    v = row_sum_step<kDppXor1>(v);
-    v = row_sum_step<kDppXor2>(v);
-    v = row_sum_step<kDppHalfMirror>(v);
-    v = row_sum_step<kDppMirror>(v);
-    v += __shfl_xor(v, 16, 64);
-    v += __shfl_xor(v, 32, 64);
-    return v;
-}
-
-// XC: 16-byte chunks of a row per lane held in registers as doubles (covers H <= 512 XC); 0: any H, the
-// token's row is re-read and re-widened for every candidate.
-template <int XC>
-__global__ __launch_bounds__(kTopkWaves * 64) void router_exact_topk_kernel(
-    RowSrc x, int64_t n_tok, int H, const bf16_t* __restrict__ wr, const float* __restrict__ bias, int E, int K, int tpw,
-    const int32_t* __restrict__ cand_cnt, const uint16_t* __restrict__ cand, int32_t* __restrict__ idx,
-    float* __restrict__ w, int32_t* __restrict__ tile_hist)
-{
-    __shared__ int32_t hist[2][kMaxExperts];
-    const int lane = lane_id();
-    const int wave = threadIdx.x >> 6;
-    const int64_t tb0 = (int64_t)blockIdx.x * (kTopkWaves * tpw);
-    const int64_t tile0 = tb0 * K / kPermTile;
-    if (tile_hist) {
-        for (int i = threadIdx.x; i < 2 * E; i += kTopkWaves * 64) hist[i / E][i % E] = 0;
-        __syncthreads();
-    }
-    const double NEG = -__builtin_huge_val();
-    const int n_chunks = H / 8;
-    auto widen = [](const u32x4_t& raw, double* out) {
-        const uint32_t d[4] = {raw.x, raw.y, raw.z, raw.w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            out[2 * i] = (double)__uint_as_float(d[i] << 16);
-            out[2 * i + 1] = (double)__uint_as_float(d[i] & 0xffff0000u);
-        }
-    };
-    for (int it = 0; it < tpw; ++it) {
-        const int64_t t = tb0 + (int64_t)wave * tpw + it;
-        if (t >= n_tok) break;
-        const bf16_t* xp = row_ptr<bf16_t>(x, t, H);
-        constexpr int XR = XC > 0 ? XC : 1;
-        double xd[XR][8];
-        if (XC > 0) {
-#pragma unroll
-            for (int i = 0; i < XC; ++i) {
-                const int ch = lane + 64 * i;
-                u32x4_t raw = {0, 0, 0, 0};
-                if (ch < n_chunks) raw = *reinterpret_cast<const u32x4_t*>(xp + ch * 8);
-                widen(raw, xd[i]);
-            }
-        }
-        const int cnt = __builtin_amdgcn_readfirstlane(cand_cnt[t]);
-        double my_z = NEG;           // lane j < K: the j-th winner so far
-        int my_e = 0x7fffffff;
-        for (int base = 0; base < cnt; base += 64) {
-            const int n_here = cnt - base < 64 ? cnt - base : 64;
-            double new_z = NEG;      // lane s: the exact logit of candidate base + s
-            int new_e = 0x7fffffff;
-            for (int s = 0; s < n_here; ++s) {
-                const int e = __builtin_amdgcn_readfirstlane((int)cand[t * E + base + s]);
-                const bf16_t* wp = wr + (int64_t)e * H;
-                double acc = 0.0;
-                if (XC > 0) {
-#pragma unroll
-                    for (int i = 0; i < XC; ++i) {
-                        const int ch = lane + 64 * i;
-                        if (ch < n_chunks) {
-                            double wd[8];
-                            widen(*reinterpret_cast<const u32x4_t*>(wp + ch * 8), wd);
-#pragma unroll
-                            for (int j = 0; j < 8; ++j) acc = fma(xd[i][j], wd[j], acc);
-                        }
-                    }
-                } else {
-                    for (int ch = lane; ch < n_chunks; ch += 64) {
-                        double xv[8], wd[8];
-                        widen(*reinterpret_cast<const u32x4_t*>(xp + ch * 8), xv);
-                        widen(*reinterpret_cast<const u32x4_t*>(wp + ch * 8), wd);
-#pragma unroll
-                        for (int j = 0; j < 8; ++j) acc = fma(xv[j], wd[j], acc);
-                    }
-                }
-                double z = wave_sum(acc);
-                if (bias) z += (double)bias[e];
-                if (lane == s) { new_z = z; new_e = e; }
-            }
-            // the K largest of (previous winners, new candidates): K rounds of a wave-wide arg-max
-            double old_z = my_z;
-            int old_e = my_e;
-            my_z = NEG;
-            my_e = 0x7fffffff;
-            for (int j = 0; j < K; ++j) {
-                double bv = new_z;
-                int be = new_e;
-                if (before(old_z, old_e, bv, be)) { bv = old_z; be = old_e; }
-                const int mine = be;
-#pragma unroll
-                for (int off = 32; off >= 1; off >>= 1) {
-                    const double ov = __shfl_xor(bv, off, 64);
-                    const int oe = __shfl_xor(be, off, 64);
-                    if (before(ov, oe, bv, be)) { bv = ov; be = oe; }
-                }
-                if (lane == j) { my_z = bv; my_e = be; }
-                if (be == mine && be != 0x7fffffff) {      // this lane held the winner: take it out
-                    if (new_e == be) { new_z = NEG; new_e = 0x7fffffff; }
-                    else { old_z = NEG; old_e = 0x7fffffff; }
-                }
-            }
-        }
-        // softmax over the K selected logits (renormalised weights)
-        const double z_max = __shfl(my_z, 0, 64);
-        const double p = (lane < K) ? exp(my_z - z_max) : 0.0;
-        double denom = p;
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) denom += __shfl_xor(denom, off, 64);
-        if (lane < K) {
-            idx[t * K + lane] = my_e;
-            w[t * K + lane] = (float)(p / denom);
-            if (tile_hist) atomicAdd(&hist[(t * K + lane) / kPermTile - tile0][my_e], 1);
-        }
-    }
-    if (tile_hist) {
-        __syncthreads();
-        for (int i = threadIdx.x; i < 2 * E; i += kTopkWaves * 64) {
-            const int c = hist[i / E][i % E];
-            if (c) atomicAdd(&tile_hist[(tile0 + i / E) * E + i % E], c);
-        }
-    }
-}
-
 hipError_t launch_router_logits(int dtype, RowSrc x, int64_t T, int H, const void* w_router, const float* bias,
                                 int E, double* logits, int32_t* zero_buf, int zero_n, hipStream_t s)
 {
@@ -707,43 +418,6 @@ hipError_t launch_topk(const double* logits, int64_t T, int E, int K, int renorm
     else if (npl <= 2) topk_kernel<2><<<grid, kTopkWaves * 64, 0, s>>>(logits, T, E, K, renorm, tpw, idx, w, tile_hist);
     else if (npl <= 4) topk_kernel<4><<<grid, kTopkWaves * 64, 0, s>>>(logits, T, E, K, renorm, tpw, idx, w, tile_hist);
     else topk_kernel<8><<<grid, kTopkWaves * 64, 0, s>>>(logits, T, E, K, renorm, tpw, idx, w, tile_hist);
-    return hipGetLastError();
-}
-
-bool router_two_pass_ok(int dtype, int renorm) { return dtype == MOE_BF16 && renorm != 0; }
-
-hipError_t launch_router_two_pass(RowSrc x, int64_t T, int H, const void* w_router, const float* bias, int E, int K,
-                                  int32_t* cand_cnt, uint16_t* cand, int32_t* idx, float* w, int32_t* tile_hist,
-                                  int32_t* zero_buf, int zero_n, hipStream_t s)
-{
-    const bf16_t* wr = (const bf16_t*)w_router;
-    const unsigned grid_a = (unsigned)((T + kScreenTokens - 1) / kScreenTokens);
-    const int ct = (E + 63) / 64;      // column tiles per wave
-#define MOE_SCREEN(N)                                                                                         \
-    {                                                                                                          \
-        const size_t lds = ((size_t)2 * kScreenTokens * (N) * 64 + kScreenTokens + (N) * 64) * sizeof(float); \
-        static bool attr_set[kMaxDevices] = {};                                                                \
-        hipError_t e = ensure_lds_limit(router_screen_kernel<N>, lds, attr_set);                              \
-        if (e != hipSuccess) return e;                                                                         \
-        router_screen_kernel<N><<<grid_a, 256, lds, s>>>(x, T, H, wr, bias, E, K, cand_cnt, cand, zero_buf, zero_n); \
-    }
-    if (ct <= 1) MOE_SCREEN(1)
-    else if (ct <= 2) MOE_SCREEN(2)
-    else if (ct <= 4) MOE_SCREEN(4)
-    else MOE_SCREEN(8)
-#undef MOE_SCREEN
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    const int tpw = T <= 2048 ? 1 : 4;
-    const unsigned grid_b = (unsigned)((T + kTopkWaves * tpw - 1) / (kTopkWaves * tpw));
-    const int xc = (H / 8 + 63) / 64;  // 16-byte chunks of a row per lane
-#define MOE_EXACT(N) router_exact_topk_kernel<N><<<grid_b, kTopkWaves * 64, 0, s>>>(x, T, H, wr, bias, E, K, tpw, cand_cnt, cand, idx, w, tile_hist)
-    if (xc <= 2) MOE_EXACT(2);
-    else if (xc <= 4) MOE_EXACT(4);
-    else if (xc <= 6) MOE_EXACT(6);
-    else if (xc <= 8) MOE_EXACT(8);
-    else MOE_EXACT(0);
-#undef MOE_EXACT
     return hipGetLastError();
 }
 
