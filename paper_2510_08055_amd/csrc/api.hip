@@ -154,6 +154,12 @@ moe_status run_layer(moe_ctx* c, const moe_layer& L, RowSrc x, int64_t T, void* 
         e = launch_topk(c->logits, T, g.E, g.K, g.renormalize, c->idx, c->w, fused_hist ? c->tile_hist : nullptr, s);
     }
     if (e != hipSuccess) return MOE_ERR_DEVICE;
+    {
+        Timed t(c, MOE_KERNEL_PERMUTE, s);
+        e = launch_permute(c->idx, A, g.E, c->counts, c->offsets, c->perm, c->inv, c->tile_hist, fused_hist,
+                           c->d_active_total, s);
+    }
+    if (e != hipSuccess) return MOE_ERR_DEVICE;
     // the activation rows are gathered inside the gate_up GEMM's tile loads: no x_perm round trip
     const bool w4 = g.weight_format == MOE_W_MXFP4;
     {

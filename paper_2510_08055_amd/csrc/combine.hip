@@ -49,7 +49,9 @@ __global__ __launch_bounds__(256) void combine_kernel(const YT* __restrict__ y_p
     __shared__ float s_w[kMaxTopK];
     const int64_t t = blockIdx.x;
     if (threadIdx.x < K) {
-        s_row[threadIdx.x] = inv[t * K + threadIdx.x];
+        // (entries are trusted to lie in [0, T K); the clamp keeps a bad one from becoming a wild address)
+        const int32_t row = inv[t * K + threadIdx.x], last = (int32_t)gridDim.x * K - 1;
+        s_row[threadIdx.x] = row < 0 ? 0 : (row > last ? last : row);
         s_w[threadIdx.x] = w[t * K + threadIdx.x];
     }
     __syncthreads();

@@ -28,7 +28,7 @@ template <int BM, int BN, bool GATED, typename OT, bool SPLIT>
 __global__ __launch_bounds__(256) void grouped_gemm_bf16_kernel(
     RowSrc X, int ldx, const int32_t* __restrict__ row_map, int map_div,
     const int32_t* __restrict__ offsets, int E, const bf16_t* __restrict__ W, int64_t w_expert_stride, int N, int K,
-    OT* __restrict__ Out, int ldo)
+    OT* __restrict__ Out, int ldo, int a_rows)
 {
     const int ldw = (SPLIT && !GATED) ? K / 2 : K;      // k-values per weight row
     constexpr int NO = GATED ? BN / 2 : BN;          // output columns per block
@@ -44,7 +44,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16_kernel(
     auto ldsB = [&](int buf) { return lds + buf * (A_ELEMS + B_ELEMS) + A_ELEMS; };
 
     const int n_tiles = (N + NO - 1) / NO;
-    const TileCoord tc = find_tile<BM>(offsets, E, n_tiles);
+    const TileCoord tc = find_tile<BM>(offsets, E, n_tiles, a_rows);
     if (!tc.valid) return;
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -61,7 +61,10 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16_kernel(
     for (int p = 0; p < A_LOADS; ++p) {
         int r = tc.row0 + ld_row + 32 * p;
         if (r >= tc.row_end) r = tc.row_end - 1;            // ragged tail: re-read a valid row, result unused
-        const int64_t src = row_map ? (int64_t)(row_map[r] / map_div) : (int64_t)r;
+        // (a row map holds indices below a_rows; the clamp keeps a bad entry from becoming a wild address)
+        int id = row_map ? row_map[r] : r;
+        id = id < 0 ? 0 : (id < a_rows ? id : a_rows - 1);
+        const int64_t src = row_map ? (int64_t)(id / map_div) : (int64_t)r;
         a_src[p] = row_ptr<bf16_t>(X, src, ldx) + ld_chunk * 8;
     }
 #pragma unroll
@@ -232,7 +235,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
     extern __shared__ __attribute__((aligned(1024))) char smem[];
 
     const int n_tiles = (N + NO - 1) / NO;
-    const TileCoord tc = find_tile<BM>(offsets, E, n_tiles);
+    const TileCoord tc = find_tile<BM>(offsets, E, n_tiles, a_rows);
     if (!tc.valid) return;
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -613,7 +616,9 @@ __global__ __launch_bounds__(256) void grouped_gemm_f32_kernel(RowSrc X, int ldx
     if (g >= A * N) return;
     const int r = (int)(g / N), n = (int)(g % N);
     const int e = expert_of_row(offsets, E, r);
-    const int64_t src = row_map ? (int64_t)(row_map[r] / map_div) : (int64_t)r;
+    int id = row_map ? row_map[r] : r;
+    id = id < 0 ? 0 : (id < A ? id : (int)A - 1);      // a bad map entry must not become a wild address
+    const int64_t src = row_map ? (int64_t)(id / map_div) : (int64_t)r;
     const float* x = row_ptr<float>(X, src, ldx);
     const float* w0 = W + (int64_t)e * w_expert_stride + (int64_t)n * K;
     float s0 = 0.f, s1 = 0.f;
@@ -663,7 +668,7 @@ static hipError_t launch_tile(RowSrc X, int ldx, const int32_t* row_map, int map
     const int64_t grid = ((m_tiles_max * n_tiles + 7) / 8) * 8;
     if (grid >= ((int64_t)1 << 31)) return hipErrorInvalidValue;   // the device-side tile search counts in 32 bits
     kern<<<(unsigned)grid, 256, lds_bytes, s>>>(X, ldx, row_map, map_div, offsets, E, W, w_expert_stride, N, K,
-                                                static_cast<OT*>(Out), ldo);
+                                                static_cast<OT*>(Out), ldo, (int)A);
     return hipGetLastError();
 }
 

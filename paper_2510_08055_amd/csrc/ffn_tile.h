@@ -32,8 +32,11 @@ struct TileCoord {
 // 32-row blocks: 1032 rows and BM = 256 give 224+224+224+192+168 rather than 4 x 256 + 8, so no block
 // streams a whole weight tile for a handful of rows.
 // (The host bounds the grid so that the tile count fits 31 bits.)
+// Offsets are trusted to be a non-decreasing sequence in [0, max_rows]; they are clamped to that range and
+// negative counts to zero all the same, so that offsets gone wrong (a caller's bug, an uninitialised buffer)
+// give wrong results inside the output's rows, never a store outside them.
 template <int BM>
-__device__ __forceinline__ TileCoord find_tile(const int32_t* __restrict__ offsets, int E, int n_tiles)
+__device__ __forceinline__ TileCoord find_tile(const int32_t* __restrict__ offsets, int E, int n_tiles, int max_rows)
 {
     constexpr int EPL = kMaxExperts / 64;
     const int lane = lane_id();
@@ -41,13 +44,15 @@ __device__ __forceinline__ TileCoord find_tile(const int32_t* __restrict__ offse
 #pragma unroll
     for (int i = 0; i <= EPL; ++i) {
         const int e = lane * EPL + i;
-        off[i] = offsets[e <= E ? e : E];
+        const int o = offsets[e <= E ? e : E];
+        off[i] = o < 0 ? 0 : (o > max_rows ? max_rows : o);
     }
     int mt[EPL];
     int sum = 0;
 #pragma unroll
     for (int i = 0; i < EPL; ++i) {
-        mt[i] = (off[i + 1] - off[i] + BM - 1) / BM;
+        const int cnt = off[i + 1] > off[i] ? off[i + 1] - off[i] : 0;
+        mt[i] = (cnt + BM - 1) / BM;
         sum += mt[i];
     }
     int incl = sum;

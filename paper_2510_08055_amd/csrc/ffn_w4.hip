@@ -115,9 +115,8 @@ __global__ __launch_bounds__(kW4Waves * 64, 2) void grouped_gemm_w4_kernel(
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     const uint32_t ldsb = lds_address(smem);    // LDS byte address of the block's dynamic shared memory
 
-    (void)a_rows;     // (same parameter list as the streaming kernel, which clamps its asynchronous row-map lookup with it)
     const int n_tiles = (N + NO - 1) / NO;
-    const TileCoord tc = find_tile<BM>(offsets, E, n_tiles);
+    const TileCoord tc = find_tile<BM>(offsets, E, n_tiles, a_rows);
     if (!tc.valid) return;
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -137,7 +136,8 @@ __global__ __launch_bounds__(kW4Waves * 64, 2) void grouped_gemm_w4_kernel(
     for (int p = 0; p < A_LPW; ++p) {
         int r = tc.row0 + (wave + NW * p) * 8 + a_lrow;
         if (r >= tc.row_end) r = tc.row_end - 1;
-        a_row_id[p] = row_map ? row_map[r] : r;
+        int id = row_map ? row_map[r] : r;
+        a_row_id[p] = id < 0 ? 0 : (id < a_rows ? id : a_rows - 1);      // a bad map entry must not become a wild address
     }
     // weights: the wave's load covers tile rows wave * 32 .. + 31, lane = (row, 16-byte MX block of the stage)
     auto weight_row = [&](int rb) {       // tile row -> row of the expert's weight matrix
@@ -417,7 +417,7 @@ __global__ __launch_bounds__(kS4Waves * 64, 4) void grouped_gemm_w4_stream_kerne
     const uint32_t ldsb = lds_address(smem);    // LDS byte address of the block's dynamic shared memory
 
     const int n_tiles = (N + NO - 1) / NO;
-    const TileCoord tc = find_tile<BM>(offsets, E, n_tiles);
+    const TileCoord tc = find_tile<BM>(offsets, E, n_tiles, a_rows);
     if (!tc.valid) return;
 
     const int tid = threadIdx.x, lane = tid & 63;
