@@ -191,8 +191,10 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16_kernel(
 // ----------------------------------------------------------------------------------------------
 // OUT_F32: the output is stored as float (the down GEMM of a context that keeps y_perm in fp32).
 // SPLIT: the intermediate is a pair of bf16 values, as in the kernel above.
+// MAPPED: the rows come through a row map (the fused gather of the gate_up GEMM); without one the look-ups and
+// their wait, a round trip to L2 at the start of every tile, are left out altogether.
 template <int RBM, int BN, int WM, int NSA, int NSB, int PBK, int MINW, int NW, int ORD, bool GATED, bool OUT_F32,
-          bool SPLIT>
+          bool SPLIT, bool MAPPED>
 __global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
     RowSrc X, int ldx, const int32_t* __restrict__ row_map, int map_div,
     const int32_t* __restrict__ offsets, int E, const bf16_t* __restrict__ W, int64_t w_expert_stride, int N, int K,
@@ -258,16 +260,15 @@ __global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
     // The lookups are loads issued from inline asm, picked up after an explicit wait further down: a
     // lookup through the compiler would be waited for with vmcnt(0) (it does not know of the asm-issued
     // weight loads that follow), i.e. together with the first weight stages out of HBM.  Until that wait
-    // the destination registers hold nothing; they are not touched in between.  Without a row map the
-    // load reads a valid dummy word (offsets[0]) and its result is ignored.
+    // the destination registers hold nothing; they are not touched in between.
     int32_t a_own[A_LPW], a_row_id[A_LPW];
 #pragma unroll
     for (int p = 0; p < A_LPW; ++p) {
         int r = tc.row0 + (wave + NW * p) * RPL + l_row;
         if (r >= tc.row_end) r = tc.row_end - 1;
         a_own[p] = r;
-        const int32_t* src = row_map ? row_map + r : offsets;
-        asm volatile("global_load_dword %0, %1, off" : "=v"(a_row_id[p]) : "v"(src) : "memory");
+        a_row_id[p] = 0;
+        if (MAPPED) asm volatile("global_load_dword %0, %1, off" : "=v"(a_row_id[p]) : "v"(row_map + r) : "memory");
     }
     const bf16_t* b_src[B_LPW];
 #pragma unroll
@@ -290,22 +291,26 @@ __global__ __launch_bounds__(NW * 64, MINW) void grouped_gemm_bf16_pipe_kernel(
         if (st < nk_)
 #pragma unroll
             for (int p = 0; p < B_LPW; ++p) issue_b(st, p);
-    // the lookups came before the weight loads of the prologue: wait for them alone
-    if (nk_ >= NSB - 1) wait_vmcnt<(NSB - 1) * B_LPW>();
-    else wait_vmcnt<0>();
+    if (MAPPED) {
+        // the lookups came before the weight loads of the prologue: wait for them alone
+        if (nk_ >= NSB - 1) wait_vmcnt<(NSB - 1) * B_LPW>();
+        else wait_vmcnt<0>();
 #pragma unroll
-    for (int p = 0; p < A_LPW; ++p) {
-        asm volatile("" : "+v"(a_row_id[p])::"memory");
-        // a row map holds indices below a_rows; the clamp keeps a bad entry from becoming a wild address
-        int32_t id = a_row_id[p] < 0 ? 0 : a_row_id[p];
-        id = id < a_rows ? id : a_rows - 1;
-        a_row_id[p] = row_map ? id : a_own[p];
+        for (int p = 0; p < A_LPW; ++p) {
+            asm volatile("" : "+v"(a_row_id[p])::"memory");
+            // a row map holds indices below a_rows; the clamp keeps a bad entry from becoming a wild address
+            int32_t id = a_row_id[p] < 0 ? 0 : a_row_id[p];
+            a_row_id[p] = id < a_rows ? id : a_rows - 1;
+        }
+    } else {
+#pragma unroll
+        for (int p = 0; p < A_LPW; ++p) a_row_id[p] = a_own[p];
     }
     const bf16_t* a_src[A_LPW];
 #pragma unroll
     for (int p = 0; p < A_LPW; ++p) {
         const int tr = (wave + NW * p) * RPL + l_row;      // row inside the tile
-        const int64_t src = row_map ? (int64_t)(a_row_id[p] / map_div) : (int64_t)a_row_id[p];
+        const int64_t src = MAPPED ? (int64_t)(a_row_id[p] / map_div) : (int64_t)a_row_id[p];
         a_src[p] = row_ptr<bf16_t>(X, src, ldx) + ((l_chunk ^ swz<PBK>(tr)) << 3);
     }
     // Loads of one stage, cut into KS parts that are issued in the shadow of the MFMAs of the KS
@@ -673,7 +678,7 @@ static hipError_t launch_tile(RowSrc X, int ldx, const int32_t* row_map, int map
 }
 
 template <int RBM, int BN, int WM, int NSA, int NSB, int PBK, int MINW, int NW, int ORD, bool GATED, bool OUT_F32,
-          bool SPLIT>
+          bool SPLIT, bool MAPPED>
 static hipError_t launch_pipe(RowSrc X, int ldx, const int32_t* row_map, int map_div, const int32_t* offsets,
                               int E, int64_t A, const bf16_t* W, int64_t w_expert_stride, int N, int K, void* Out,
                               int ldo, hipStream_t s)
@@ -681,7 +686,7 @@ static hipError_t launch_pipe(RowSrc X, int ldx, const int32_t* row_map, int map
     constexpr int BM = RBM * 32;
     constexpr int NO = GATED ? BN / 2 : BN;
     const size_t lds_bytes = ((size_t)NSA * BM + (size_t)NSB * BN) * PBK * 2;
-    auto kern = grouped_gemm_bf16_pipe_kernel<RBM, BN, WM, NSA, NSB, PBK, MINW, NW, ORD, GATED, OUT_F32, SPLIT>;
+    auto kern = grouped_gemm_bf16_pipe_kernel<RBM, BN, WM, NSA, NSB, PBK, MINW, NW, ORD, GATED, OUT_F32, SPLIT, MAPPED>;
     static bool attr_set[kMaxDevices] = {};
     hipError_t e = ensure_lds_limit(kern, lds_bytes, attr_set);
     if (e != hipSuccess) return e;
@@ -704,11 +709,18 @@ static hipError_t launch_bf16(int variant, RowSrc X, int ldx, const int32_t* row
     // block's prologue and epilogue are covered by the other's loads, and the many small tiles balance
     // well over the chip.  compute bound: 256 x 256 tiles, 8 waves (2 per SIMD: one wave's barrier and
     // LDS waits are covered by the other's MFMAs), 2 (rows) x 4 (columns).
+    // (only the gate_up GEMM is ever called with a row map)
+    const bool mapped = GATED && row_map != nullptr;
+    if (!GATED && row_map != nullptr) return hipErrorInvalidValue;
     switch (pick_variant(variant, A, E, (SPLIT && !GATED) ? K / 2 : K)) {
         case V_PIPE_SMALL:
-            return launch_pipe<2, 128, 2, 3, 3, 64, 2, 4, 0, GATED, OUT_F32, SPLIT>(X, ldx, row_map, map_div, offsets, E, A, W, w_expert_stride, N, K, Out, ldo, s);
+            if (mapped)
+                return launch_pipe<2, 128, 2, 3, 3, 64, 2, 4, 0, GATED, OUT_F32, SPLIT, GATED>(X, ldx, row_map, map_div, offsets, E, A, W, w_expert_stride, N, K, Out, ldo, s);
+            return launch_pipe<2, 128, 2, 3, 3, 64, 2, 4, 0, GATED, OUT_F32, SPLIT, false>(X, ldx, row_map, map_div, offsets, E, A, W, w_expert_stride, N, K, Out, ldo, s);
         case V_PIPE_BIG:
-            return launch_pipe<8, 256, 2, 2, 3, 64, 2, 8, 3, GATED, OUT_F32, SPLIT>(X, ldx, row_map, map_div, offsets, E, A, W, w_expert_stride, N, K, Out, ldo, s);
+            if (mapped)
+                return launch_pipe<8, 256, 2, 2, 3, 64, 2, 8, 3, GATED, OUT_F32, SPLIT, GATED>(X, ldx, row_map, map_div, offsets, E, A, W, w_expert_stride, N, K, Out, ldo, s);
+            return launch_pipe<8, 256, 2, 2, 3, 64, 2, 8, 3, GATED, OUT_F32, SPLIT, false>(X, ldx, row_map, map_div, offsets, E, A, W, w_expert_stride, N, K, Out, ldo, s);
         default:
             if (OUT_F32)
                 return launch_tile<128, 128, GATED, float, SPLIT>(X, ldx, row_map, map_div, offsets, E, A, W,
