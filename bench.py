@@ -70,6 +70,9 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--time-all-kernels", action="store_true",
                     help="bracket all six kernels of a layer with events (default: the two grouped GEMMs)")
+    ap.add_argument("--ffn-variant", default="auto",
+                    choices=["auto", "tile128", "small", "big", "w4_tile64", "w4_stream"],
+                    help="tuning aid: pin the grouped-GEMM kernel shape (moe_set_ffn_variant); auto = the library's own choice")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy kernel a few times (reference for scaling "
                          "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run) and exit")
@@ -118,6 +121,8 @@ def measure(args, name, schedule, steps, warmup, cpu_baseline):
     wsz = 17.0 / 32.0 if w.weight_format == "mxfp4" else esz       # bytes per expert-weight element (codes + scales)
     act_sz = esz * (2 if w.act_split else 1)                        # bytes per element of the intermediate
     y_sz = 4 if (w.y_perm_f32 or w.dtype == "f32") else 2           # bytes per element of y_perm
+    if args.ffn_variant != "auto":
+        ctx.moe_set_ffn_variant(args.ffn_variant)
     packed = ctx.pack_layers(layers)
     yd = torch.empty((w.D, w.H), dtype=dt, device=dev)
     yp = torch.empty((w.P, w.H), dtype=dt, device=dev)
@@ -270,7 +275,8 @@ def measure(args, name, schedule, steps, warmup, cpu_baseline):
                    "groups": args.groups if stack else None, "granule": args.granule if stack else None, "H": w.H, "E": w.E,
                    "top_k": w.K, "I": w.I, "layers": w.n_layers, "decode_tokens": w.D, "prefill_tokens": w.P, "seed": w.seed,
                    "route_skew": w.route_skew, "weight_format": w.weight_format or w.dtype,
-                   "y_perm": "f32" if y_sz == 4 else "bf16", "intermediate": "bf16 pair" if w.act_split else w.dtype},
+                   "y_perm": "f32" if y_sz == 4 else "bf16", "intermediate": "bf16 pair" if w.act_split else w.dtype,
+                   "ffn_variant": args.ffn_variant},
         "roofline": roofline,
         "kernels": kernels,
         "step": {"bound": bound, "achieved": round(s_ach, 2), "unit": s_unit, "frac": round(s_ach / s_peak, 4),
