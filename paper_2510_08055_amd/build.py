@@ -30,7 +30,7 @@ def _scratch_users(log, names):
     """Kernels (mangled names containing one of `names`) whose resource remarks report scratch or spills."""
     bad, cur = [], None
     for line in log.splitlines():
-        if "remark: Function Name:" in line:
+        if "Function Name:" in line:       # "remark: <file>:<line>:<col>: Function Name: ..." or "<file>:<line>:<col>: remark: Function Name: ..."
             cur = line.split("Function Name:")[1].split()[0]
         elif cur and any(n in cur for n in names):
             for key in ("ScratchSize [bytes/lane]:", "VGPRs Spill:"):

@@ -140,6 +140,12 @@ def test_build_rejects_scratch_in_kernels_with_asynchronous_loads():
     assert len(found) == 2 and "836" in found[0] and "2072" in found[1]
     other = bad.replace("grouped_gemm_w4_stream_kernel", "some_other_kernel")
     assert build._scratch_users(other, ("grouped_gemm_w4_stream_kernel",)) == []
+    # the same remarks as the compiler words them when it also keeps its intermediate files (-save-temps)
+    bad2 = ("remark: x.hip:202:0: Function Name: _ZN3moe29grouped_gemm_bf16_pipe_kernelILi8ELi256EEEv [-Rpass-analysis]\n"
+            "remark: x.hip:202:0:     ScratchSize [bytes/lane]: 104 [-Rpass-analysis]\n"
+            "remark: x.hip:202:0:     VGPRs Spill: 25 [-Rpass-analysis]\n")
+    found = build._scratch_users(bad2, ("grouped_gemm_bf16_pipe_kernel",))
+    assert len(found) == 2 and "104" in found[0] and "25" in found[1]
 
 
 def test_build_rejects_m0_uses_outside_the_asm_issued_lds_loads():
