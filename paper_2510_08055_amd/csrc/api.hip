@@ -319,7 +319,7 @@ moe_status moe_router_topk_noalloc(const moe_config* cfg, const void* x, int64_t
     moe_status st = check_cfg(cfg);
     if (st != MOE_OK) return st;
     if (T < 0) return MOE_ERR_SHAPE;
-    if (T * (int64_t)cfg->E > kNoallocMaxLogits) return MOE_ERR_WORKSPACE;      // the static scratch holds T * E logits
+    if (T > kNoallocMaxLogits / cfg->E) return MOE_ERR_WORKSPACE;      // the static scratch holds T * E logits (no overflow for any T)
     if (T == 0) return MOE_OK;
     if (!x || !w_router || !topk_idx || !topk_w) return MOE_ERR_NULL;
     if (misaligned(x) || misaligned(w_router)) return MOE_ERR_ALIGN;

@@ -91,6 +91,7 @@ def test_router_topk_noalloc_rejects_bad_arguments_before_touching_the_gpu():
     assert lib.moe_router_topk_noalloc(None, fake, 4, fake, None, fake, fake, None) == 1
     assert lib.moe_router_topk_noalloc(ctypes.byref(cfg), fake, -1, fake, None, fake, fake, None) == 2
     assert lib.moe_router_topk_noalloc(ctypes.byref(cfg), fake, 4097, fake, None, fake, fake, None) == 5   # 4097 * 128 logits
+    assert lib.moe_router_topk_noalloc(ctypes.byref(cfg), fake, 2 ** 62, fake, None, fake, fake, None) == 5   # T * E overflows 64 bits
     assert lib.moe_router_topk_noalloc(ctypes.byref(cfg), None, 4, fake, None, fake, fake, None) == 1
     assert lib.moe_router_topk_noalloc(ctypes.byref(cfg), ctypes.c_void_p(0x10008), 4, fake, None, fake, fake, None) == 4
     assert lib.moe_router_topk_noalloc(ctypes.byref(cfg), None, 0, None, None, None, None, None) == 0      # no rows: a no-op
