@@ -244,7 +244,7 @@ moe_status moe_workspace_bytes(const moe_config* cfg, int64_t max_tokens, size_t
     if (!out_bytes) return MOE_ERR_NULL;
     moe_status st = check_cfg(cfg);
     if (st != MOE_OK) return st;
-    if (max_tokens <= 0 || max_tokens * (int64_t)cfg->K >= (int64_t)1 << 31) return MOE_ERR_SHAPE;
+    if (max_tokens <= 0 || max_tokens > (((int64_t)1 << 31) - 1) / cfg->K) return MOE_ERR_SHAPE;   // A = T*K is counted in 32 bits
     *out_bytes = carve(*cfg, max_tokens).total;
     return MOE_OK;
 }
@@ -255,7 +255,7 @@ moe_status moe_create(const moe_config* cfg, int64_t max_tokens, void* workspace
     if (!out_ctx || !workspace) return MOE_ERR_NULL;
     moe_status st = check_cfg(cfg);
     if (st != MOE_OK) return st;
-    if (max_tokens <= 0 || max_tokens * (int64_t)cfg->K >= (int64_t)1 << 31) return MOE_ERR_SHAPE;
+    if (max_tokens <= 0 || max_tokens > (((int64_t)1 << 31) - 1) / cfg->K) return MOE_ERR_SHAPE;   // A = T*K is counted in 32 bits
     if (reinterpret_cast<uintptr_t>(workspace) % kAlign) return MOE_ERR_ALIGN;
     const Layout L = carve(*cfg, max_tokens);
     if (workspace_bytes < L.total) return MOE_ERR_WORKSPACE;

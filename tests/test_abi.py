@@ -49,6 +49,8 @@ def test_workspace_bytes_and_argument_errors():
     assert _ws(E=0)[0] == 2
     assert _ws(E=4096)[0] == 2
     assert _ws(T=0)[0] == 2
+    assert _ws(T=2 ** 30)[0] == 2 and _ws(T=2 ** 62)[0] == 2      # T*K must fit 31 bits, whatever T (no wrap-around)
+    assert _ws(T=2 ** 30 - 1)[0] == 0
     assert _ws(dtype=7)[0] == 3      # unknown dtype    -> MOE_ERR_DTYPE
     assert _ws(H=257)[0] == 4        # H % 8 != 0       -> MOE_ERR_ALIGN
     assert _ws(I=12)[0] == 4
