@@ -353,8 +353,9 @@ moe_status moe_permute(moe_ctx* ctx, const void* x, const int32_t* topk_idx, int
     hipStream_t s = static_cast<hipStream_t>(stream);
     const moe_config& g = ctx->cfg;
     if (T == 0) {
-        if (hipMemsetAsync(counts, 0, sizeof(int32_t) * g.E, s) != hipSuccess) return MOE_ERR_DEVICE;
-        return dev(hipMemsetAsync(offsets, 0, sizeof(int32_t) * (g.E + 1), s));
+        // fill kernels, not memset nodes: the caller may be capturing the stream
+        if (launch_fill_zero(counts, g.E, s) != hipSuccess) return MOE_ERR_DEVICE;
+        return dev(launch_fill_zero(offsets, g.E + 1, s));
     }
     if (!topk_idx || !perm || !inv_perm) return MOE_ERR_NULL;
     if (x_perm && (!x || misaligned(x) || misaligned(x_perm))) return x ? MOE_ERR_ALIGN : MOE_ERR_NULL;
@@ -529,7 +530,7 @@ moe_status moe_reset_counters(moe_ctx* ctx, void* stream)
     if (!ctx) return MOE_ERR_NULL;
     ctx->router_bytes = ctx->tokens_processed = 0;
     ctx->iterations = ctx->layer_passes = 0;
-    return dev(hipMemsetAsync(ctx->d_active_total, 0, sizeof(unsigned long long), static_cast<hipStream_t>(stream)));
+    return dev(launch_fill_zero(ctx->d_active_total, 2, static_cast<hipStream_t>(stream)));
 }
 
 moe_status moe_kernel_timing(moe_ctx* ctx, uint32_t kernel_mask)

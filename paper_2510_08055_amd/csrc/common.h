@@ -68,6 +68,7 @@ constexpr int kPermTile = 8192;  // assignments per block of the permutation ker
 hipError_t launch_permute(const int32_t* idx, int64_t A, int E, int32_t* counts, int32_t* offsets,
                           int32_t* perm, int32_t* inv, int32_t* tile_hist, bool hist_ready,
                           unsigned long long* active_total, hipStream_t s);
+hipError_t launch_fill_zero(void* p, int n_words, hipStream_t s);   // a fill kernel, not a memset node
 hipError_t launch_gather_rows(int dtype, const void* x, const int32_t* perm, int K, int64_t A, int H,
                               void* x_perm, hipStream_t s);
 

@@ -198,6 +198,21 @@ hipError_t launch_permute(const int32_t* idx, int64_t A, int E, int32_t* counts,
     return hipGetLastError();
 }
 
+// Zeroes n 32-bit words.  In place of hipMemsetAsync wherever a caller may be capturing the stream into a
+// HIP graph (memset nodes have replayed wrongly on this platform).
+__global__ __launch_bounds__(256) void fill_zero_kernel(uint32_t* __restrict__ p, int n)
+{
+    const int i = (int)(blockIdx.x * 256 + threadIdx.x);
+    if (i < n) p[i] = 0u;
+}
+
+hipError_t launch_fill_zero(void* p, int n_words, hipStream_t s)
+{
+    if (n_words <= 0) return hipSuccess;
+    fill_zero_kernel<<<(unsigned)((n_words + 255) / 256), 256, 0, s>>>(static_cast<uint32_t*>(p), n_words);
+    return hipGetLastError();
+}
+
 hipError_t launch_gather_rows(int dtype, const void* x, const int32_t* perm, int K, int64_t A, int H, void* x_perm,
                               hipStream_t s)
 {

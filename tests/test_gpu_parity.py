@@ -88,6 +88,27 @@ def test_permute_bit_exact(gpu_lib, T, K, E):
     assert torch.equal(again[2], perm) and torch.equal(again[3], inv)
 
 
+def test_step_calls_on_an_empty_batch(gpu_lib):
+    """No rows: every step call is a no-op, except that the permutation still reports E zero counts and E + 1 zero
+    offsets (written by a fill kernel, so that the call stays capturable)."""
+    H, E, K, I = 128, 8, 2, 64
+    ctx = gpu_lib.Context(H, E, K, I, torch.bfloat16, max_tokens=16, device=DEV)
+    x = torch.zeros((0, H), dtype=torch.bfloat16, device=DEV)
+    wr = inputs.randn((E, H), 0.02, 5, "wr", 0, "bf16").to(DEV)
+    idx, w = ctx.moe_router_topk(x, wr)
+    assert idx.shape == (0, K) and w.shape == (0, K)
+    counts, offsets, perm, inv, x_perm = ctx.moe_permute(x, idx)
+    assert counts.shape == (E,) and offsets.shape == (E + 1,)
+    assert int(counts.abs().sum()) == 0 and int(offsets.abs().sum()) == 0
+    assert perm.numel() == 0 and inv.numel() == 0 and x_perm.shape == (0, H)
+    wg = torch.zeros((E, 2 * I, H), dtype=torch.bfloat16, device=DEV)
+    wd = torch.zeros((E, H, I), dtype=torch.bfloat16, device=DEV)
+    y_perm = ctx.moe_grouped_ffn(x_perm, offsets, wg, wd)
+    assert y_perm.shape == (0, H)
+    y = ctx.moe_combine(y_perm, inv, w)
+    assert y.shape == (0, H)
+
+
 # ------------------------------------------------------------- grouped FFN and combine
 @pytest.mark.parametrize("H,I,E,rows,dtype", [
     (256, 512, 4, [130, 0, 1, 64], "bf16"),       # an empty expert, a 1-row expert, a ragged tile
