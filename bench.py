@@ -299,7 +299,7 @@ def main():
     args = parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py measures the single-GPU hot path only: this build has no multi-GPU path "
-              "(run with --gpus 1; see DESIGN.md for how the path would shard)", file=sys.stderr)
+              "(run with --gpus 1; value is the one GPU's throughput)", file=sys.stderr)
         sys.exit(2)
 
     import torch
